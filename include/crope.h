@@ -1,0 +1,152 @@
+/*
+ * crope.h — C ABI of the per-chunk attention step of causal autoregressive video-DiT
+ * inference with Causal-RoPE, for AMD MI355X (gfx950).
+ *
+ * The three operations follow the optimized sequence-parallel self-attention call of the
+ * paper (Algorithm 3): step 2/3 (global token offset, causal 3D RoPE computed locally
+ * from the global start frame), step 5 (KV-cache update) and step 6 (attention of the
+ * chunk's queries over the whole cache).  The projection (step 1) and the collectives
+ * (steps 4, 7) are outside this library.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers to caller-owned memory unless a parameter is
+ *     documented as host memory.  The library never allocates, frees or keeps a pointer
+ *     after the call's work has been enqueued.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued and the call returns; there is no implicit synchronisation.  Calls issued
+ *     back to back on one stream execute in order (append, then attention).
+ *   - Return value: CROPE_OK (0) or a negative error code.  On error nothing has been
+ *     launched and crope_last_error() returns a thread-local, human-readable message.
+ *   - Activations are bf16, laid out [token][head][128] with the 128 head channels
+ *     contiguous; token and head strides are given in elements.
+ */
+#ifndef CROPE_H
+#define CROPE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  CROPE_OK = 0,
+  CROPE_EINVAL = -1,     /* null pointer, non-positive size, bad enum value            */
+  CROPE_ESHAPE = -2,     /* head_dim != 128, odd axis width, widths not summing to 128 */
+  CROPE_EALIGN = -3,     /* base pointer or stride not 16-byte aligned                 */
+  CROPE_ERANGE = -4,     /* position beyond table extent, rows beyond cache capacity   */
+  CROPE_EWORKSPACE = -5, /* workspace missing or too small                             */
+  CROPE_EHIP = -6        /* the HIP runtime reported a launch error                    */
+};
+
+/* Immutable description of the rotary tables (host memory, passed by pointer).
+ * Within a head, channel pairs (2j, 2j+1) are rotated; the first dim_t/2 pairs take the
+ * temporal angle, the next dim_h/2 the height angle, the last dim_w/2 the width angle
+ * (Algorithm 2: concatenation of the time, height and width frequency slices). */
+typedef struct {
+  int32_t head_dim;            /* must be 128                                          */
+  int32_t dim_t, dim_h, dim_w; /* channels per axis: even, sum == head_dim (44/42/42)  */
+  double theta;                /* rotary base, 10000                                   */
+  int32_t max_t, max_h, max_w; /* table extents: valid positions are 0..max-1          */
+} crope_table_desc;
+
+/* Strides of a [token][head][128] bf16 tensor, in elements; channel stride is 1. */
+typedef struct {
+  int64_t token;
+  int64_t head;
+} crope_strides;
+
+/* A run of consecutive cache rows (tokens) visible to attention. */
+typedef struct {
+  int64_t start;
+  int64_t len;
+} crope_kv_segment;
+
+/* Size in bytes of the table buffer for `desc` (0 if desc is invalid).  Layout: three
+ * contiguous fp32 arrays, time [max_t][dim_t/2][2], height [max_h][dim_h/2][2], width
+ * [max_w][dim_w/2][2]; innermost pair is (cos, sin) of pos * theta^(-2j/dim_axis). */
+size_t crope_table_bytes(const crope_table_desc* desc);
+
+/* Precompute the rotary tables once, into contiguous device memory, so that no host
+ * work or cache lookup remains on the per-chunk path (Section 3.4.1 item 2; the per-axis
+ * tables are Algorithm 2's freqs[0..2]).  Angles are formed in fp64 on the device and
+ * rounded once to fp32.
+ *   d_table  device, `bytes` >= crope_table_bytes(desc), 16-byte aligned; overwritten. */
+int crope_build_table(const crope_table_desc* desc, float* d_table, size_t bytes,
+                      void* stream);
+
+/* Fused qk-RMSNorm + causal 3D RoPE + KV-cache update for one call's local token rows
+ * (Algorithm 3 steps 2, 3 and 5; position rule of Section 3.3.3).
+ *
+ * Row i of the inputs is token i_global = token_offset + i of the current chunk, whose
+ * position is t_global = start_frame + i_global / (grid_h*grid_w), h = (i_global mod
+ * grid_h*grid_w) / grid_w, w = i_global mod grid_w.  q and k are RMS-normalised (fp32
+ * statistics over `norm_group` channels, times a learned gain), rotated, rounded once to
+ * bf16; rotated q goes to q_out, rotated k and the untouched v are ASSIGNED to cache rows
+ * [dst_token, dst_token + n_tokens) (rewriting rows is how repeated denoising passes and
+ * a rolling window work; the caller picks dst_token).
+ *
+ *   desc, d_table   as built by crope_build_table
+ *   q, k, v         device bf16 [n_tokens][n_heads][128], strides `in` (shared by all three)
+ *   gain_q, gain_k  device fp32 [n_heads*128]
+ *   eps             RMSNorm epsilon
+ *   norm_group      n_heads*128 (statistics over the token's whole projection vector)
+ *                   or 128 (per head)
+ *   grid_h, grid_w  latent token grid of one frame; must be <= max_h, max_w
+ *   start_frame     s, global index of the chunk's first frame
+ *   token_offset    Delta = rank * (chunk tokens / ranks); 0 on one GPU
+ *   q_out           device bf16 [n_tokens][n_heads][128], strides q_out_strides
+ *   k_cache,v_cache device bf16 [cache_capacity_tokens][n_heads][128], strides cache_strides
+ * Errors: CROPE_ERANGE if any row's t_global >= max_t or dst_token + n_tokens exceeds the
+ * capacity; CROPE_EALIGN unless every base pointer and stride*2 bytes is a multiple of 16.
+ * n_tokens == 0 is a no-op that returns CROPE_OK.  Input and output buffers must not
+ * overlap, except that q_out may alias q. */
+int crope_qk_norm_rotate_append(
+    const crope_table_desc* desc, const float* d_table,
+    const void* q, const void* k, const void* v, crope_strides in,
+    const float* gain_q, const float* gain_k, float eps, int32_t norm_group,
+    int32_t n_tokens, int32_t n_heads, int32_t grid_h, int32_t grid_w,
+    int32_t start_frame, int32_t token_offset,
+    void* q_out, crope_strides q_out_strides,
+    void* k_cache, void* v_cache, crope_strides cache_strides,
+    int64_t cache_capacity_tokens, int64_t dst_token, void* stream);
+
+/* Bytes of scratch chunk_attention needs for this problem size (may be 0). */
+size_t chunk_attention_workspace_bytes(int32_t n_q, int32_t n_heads, int64_t n_keys);
+
+/* Attention of the chunk's rotated queries over every visible cache row (Algorithm 3
+ * step 6): per head and query, softmax(scale * q.K^T) V over the union of `segs`.  There
+ * is no element mask: causality comes from what the cache holds (the chunk is the causal
+ * block, so its queries see all cached keys and all keys of their own chunk).  bf16 MFMA
+ * with fp32 accumulation and fp32 online softmax; probabilities are rounded to bf16 for
+ * the second product.
+ *
+ *   q              device bf16 [n_q][n_heads][128] (already rotated), strides q_strides
+ *   k_cache,v_cache device bf16 caches, strides cache_strides
+ *   segs           HOST array of n_segs (1..4) row ranges; 2 when a ring cache wraps.
+ *                  Ranges must lie inside [0, cache_capacity_tokens) and have len > 0.
+ *   scale          softmax scale (1/sqrt(128) for the model this follows)
+ *   out            device bf16 [n_q][n_heads][128], strides out_strides
+ *   lse_or_null    device fp32 [n_heads][n_q], natural-log sum-exp of the scaled scores
+ *   workspace      device scratch of >= chunk_attention_workspace_bytes(...) bytes, 16-byte
+ *                  aligned; may be NULL when that size is 0.  Contents are undefined after.
+ * n_q == 0 is a no-op. */
+int chunk_attention(
+    const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
+    const void* k_cache, const void* v_cache, crope_strides cache_strides,
+    int64_t cache_capacity_tokens,
+    const crope_kv_segment* segs, int32_t n_segs, float scale,
+    void* out, crope_strides out_strides, float* lse_or_null,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Thread-local message describing the last error returned on this thread ("" if none). */
+const char* crope_last_error(void);
+
+/* Library version string, e.g. "crope 0.1 (gfx950)". */
+const char* crope_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CROPE_H */

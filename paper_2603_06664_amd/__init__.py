@@ -1,0 +1,11 @@
+"""MI355X-native Causal-RoPE + chunk attention (hand-written HIP behind a C ABI).
+
+``binding`` holds the ctypes marshalling for the calls declared in include/crope.h;
+``workloads`` the seeded synthetic inputs; ``build`` compiles libcrope.so with hipcc.
+Importing the package does not load the library; the first call does, and fails loudly
+if it cannot.
+"""
+from .binding import (  # noqa: F401
+    CropeError, TableDesc, chunk_attention, chunk_attention_workspace_bytes, crope_build_table,
+    crope_last_error, crope_qk_norm_rotate_append, crope_table_bytes, crope_version, library_path,
+)

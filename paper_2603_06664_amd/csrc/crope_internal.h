@@ -1,0 +1,66 @@
+// Internal launch interface between the host-side ABI (crope_api.hip) and the kernels.
+// Not installed; include/crope.h is the public boundary.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/crope.h"
+
+namespace crope {
+
+constexpr int kHeadDim = 128;
+constexpr int kMaxSegments = 4;
+
+struct TableLayout {
+  int pairs_t, pairs_h, pairs_w;      // dim_axis / 2
+  int max_t, max_h, max_w;
+  // offsets in floats from the table base
+  int64_t off_t, off_h, off_w, total_floats;
+};
+
+inline TableLayout table_layout(const crope_table_desc& d) {
+  TableLayout L;
+  L.pairs_t = d.dim_t / 2; L.pairs_h = d.dim_h / 2; L.pairs_w = d.dim_w / 2;
+  L.max_t = d.max_t; L.max_h = d.max_h; L.max_w = d.max_w;
+  L.off_t = 0;
+  L.off_h = L.off_t + (int64_t)d.max_t * L.pairs_t * 2;
+  L.off_w = L.off_h + (int64_t)d.max_h * L.pairs_h * 2;
+  L.total_floats = L.off_w + (int64_t)d.max_w * L.pairs_w * 2;
+  return L;
+}
+
+struct RopeArgs {
+  const float* table; TableLayout tl;
+  const uint16_t *q, *k, *v;
+  int64_t in_tok, in_head;
+  const float *gain_q, *gain_k;
+  float eps; int per_head_norm;
+  int n_tokens, n_heads, grid_h, grid_w, start_frame, token_offset;
+  uint16_t* q_out; int64_t qo_tok, qo_head;
+  uint16_t *k_cache, *v_cache; int64_t c_tok, c_head;
+  int64_t dst_token;
+};
+
+struct Segments {
+  int n;
+  int64_t start[kMaxSegments];
+  int64_t len[kMaxSegments];
+};
+
+struct AttnArgs {
+  const uint16_t* q; int64_t q_tok, q_head;
+  int n_q, n_heads;
+  const uint16_t *k_cache, *v_cache; int64_t c_tok, c_head;
+  Segments segs; int64_t n_keys;
+  float scale;
+  uint16_t* out; int64_t o_tok, o_head;
+  float* lse;
+  void* workspace; size_t workspace_bytes;
+};
+
+hipError_t launch_build_table(const crope_table_desc& d, float* table, hipStream_t st);
+hipError_t launch_rope(const RopeArgs& a, hipStream_t st);
+int rope_max_heads();
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
+size_t attention_workspace_bytes(int n_q, int n_heads, int64_t n_keys);
+
+}  // namespace crope

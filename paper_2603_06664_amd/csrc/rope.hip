@@ -1,0 +1,225 @@
+// Rotary table build and the fused qk-RMSNorm + causal 3D RoPE + KV-cache update kernel.
+//
+// The fused kernel is bandwidth-bound: per token it reads q, k, v (3 * H*128 bf16) and
+// writes rotated q, rotated k, v (another 3 * H*128 bf16).  One 64-lane wave owns one token;
+// every lane moves 16-byte pieces (8 channels of one head), so a wave's requests cover
+// whole contiguous 1 KB spans.  Statistics are fp32, reduced across the wave with
+// cross-lane shuffles; nothing is staged through LDS.
+#include "crope_internal.h"
+
+namespace crope {
+namespace {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  f32x2_t f = {lo, hi};
+  bf16x2_t h = __builtin_convertvector(f, bf16x2_t);  // v_cvt_pk_bf16_f32, round-nearest-even
+  return __builtin_bit_cast(uint32_t, h);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// ---------------------------------------------------------------- table build
+// One thread per (axis, position, pair).  The angle pos * theta^(-2j/dim) is formed in
+// fp64 (an fp32 product would already be off by ~1e-4 rad at pos ~ 1000) and rounded once.
+__global__ void build_table_kernel(float* __restrict__ table, TableLayout tl, int dim_t, int dim_h,
+                                   int dim_w, double theta) {
+  const int64_t n_t = (int64_t)tl.max_t * tl.pairs_t;
+  const int64_t n_h = (int64_t)tl.max_h * tl.pairs_h;
+  const int64_t n_w = (int64_t)tl.max_w * tl.pairs_w;
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n_t + n_h + n_w) return;
+  int pairs, dim;
+  int64_t off;
+  if (idx < n_t) { pairs = tl.pairs_t; dim = dim_t; off = tl.off_t; }
+  else if (idx < n_t + n_h) { idx -= n_t; pairs = tl.pairs_h; dim = dim_h; off = tl.off_h; }
+  else { idx -= n_t + n_h; pairs = tl.pairs_w; dim = dim_w; off = tl.off_w; }
+  const int pos = (int)(idx / pairs);
+  const int j = (int)(idx % pairs);
+  const double omega = pow(theta, -2.0 * (double)j / (double)dim);
+  const double phi = (double)pos * omega;
+  double s, c;
+  sincos(phi, &s, &c);
+  float2 cs = make_float2((float)c, (float)s);
+  reinterpret_cast<float2*>(table + off)[idx] = cs;
+}
+
+// ---------------------------------------------------------------- fused kernel
+constexpr int kWavesPerBlock = 4;
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+  return x;
+}
+__device__ __forceinline__ float group16_sum(float x) {
+#pragma unroll
+  for (int m = 8; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+  return x;
+}
+
+// ITERS = ceil(n_heads / 4): lane l owns 16-byte chunk c = l + 64*it of the token's H*16
+// chunks; chunk c is head c/16, channels 8*(c%16)..+7, and c%16 == l%16 for every it, so a
+// lane's four rotation angles are the same for all of its chunks.
+template <int ITERS>
+__global__ __launch_bounds__(64 * kWavesPerBlock) void rope_kernel(RopeArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int tok = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  if (tok >= a.n_tokens) return;
+  const int n_chunks = a.n_heads * 16;
+
+  // issue all loads first: q, k, v chunks of this lane
+  uint4 rq[ITERS], rk[ITERS], rv[ITERS];
+  const int64_t in_base = (int64_t)tok * a.in_tok;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int c = lane + 64 * it;
+    if (c < n_chunks) {
+      const int64_t off = in_base + (int64_t)(c >> 4) * a.in_head + (c & 15) * 8;
+      rq[it] = *reinterpret_cast<const uint4*>(a.q + off);
+      rk[it] = *reinterpret_cast<const uint4*>(a.k + off);
+      rv[it] = *reinterpret_cast<const uint4*>(a.v + off);
+    } else {
+      rq[it] = make_uint4(0, 0, 0, 0); rk[it] = rq[it]; rv[it] = rq[it];
+    }
+  }
+
+  // global position of this token (index decode with the global time index)
+  const int hw = a.grid_h * a.grid_w;
+  const int ig = a.token_offset + tok;
+  const int f = ig / hw;
+  const int r = ig - f * hw;
+  const int ph = r / a.grid_w;
+  const int pw = r - ph * a.grid_w;
+  const int pt = a.start_frame + f;
+
+  // the lane's four (cos, sin) pairs: pair index j = 4*(lane%16) + p
+  float cs[4], sn[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int j = 4 * (lane & 15) + p;
+    const float* src;
+    if (j < a.tl.pairs_t) src = a.table + a.tl.off_t + ((int64_t)pt * a.tl.pairs_t + j) * 2;
+    else if (j < a.tl.pairs_t + a.tl.pairs_h)
+      src = a.table + a.tl.off_h + ((int64_t)ph * a.tl.pairs_h + (j - a.tl.pairs_t)) * 2;
+    else
+      src = a.table + a.tl.off_w + ((int64_t)pw * a.tl.pairs_w + (j - a.tl.pairs_t - a.tl.pairs_h)) * 2;
+    const float2 t = *reinterpret_cast<const float2*>(src);
+    cs[p] = t.x; sn[p] = t.y;
+  }
+
+  // v goes to the cache untouched
+  const int64_t c_base = (a.dst_token + tok) * a.c_tok;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int c = lane + 64 * it;
+    if (c < n_chunks)
+      *reinterpret_cast<uint4*>(a.v_cache + c_base + (int64_t)(c >> 4) * a.c_head + (c & 15) * 8) = rv[it];
+  }
+
+  // sums of squares
+  float ssq[ITERS], ssk[ITERS];
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const uint32_t* uq = reinterpret_cast<const uint32_t*>(&rq[it]);
+    const uint32_t* uk = reinterpret_cast<const uint32_t*>(&rk[it]);
+    float sq = 0.f, sk = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float x0 = bf16_lo(uq[e]), x1 = bf16_hi(uq[e]);
+      float y0 = bf16_lo(uk[e]), y1 = bf16_hi(uk[e]);
+      sq = fmaf(x0, x0, sq); sq = fmaf(x1, x1, sq);
+      sk = fmaf(y0, y0, sk); sk = fmaf(y1, y1, sk);
+    }
+    ssq[it] = sq; ssk[it] = sk;
+  }
+  float rq_scale[ITERS], rk_scale[ITERS];
+  if (a.per_head_norm) {
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const float tq = group16_sum(ssq[it]);
+      const float tk = group16_sum(ssk[it]);
+      rq_scale[it] = 1.0f / sqrtf(tq * (1.0f / kHeadDim) + a.eps);
+      rk_scale[it] = 1.0f / sqrtf(tk * (1.0f / kHeadDim) + a.eps);
+    }
+  } else {
+    float tq = 0.f, tk = 0.f;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) { tq += ssq[it]; tk += ssk[it]; }
+    tq = wave_sum(tq); tk = wave_sum(tk);
+    const float inv_n = 1.0f / (float)(a.n_heads * kHeadDim);
+    const float sq = 1.0f / sqrtf(tq * inv_n + a.eps);
+    const float sk = 1.0f / sqrtf(tk * inv_n + a.eps);
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) { rq_scale[it] = sq; rk_scale[it] = sk; }
+  }
+
+  // normalise, apply gain, rotate, round once to bf16, store
+  const int64_t qo_base = (int64_t)tok * a.qo_tok;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int c = lane + 64 * it;
+    if (c >= n_chunks) continue;
+    const int head = c >> 4, d0 = (c & 15) * 8;
+    const float4 gq0 = *reinterpret_cast<const float4*>(a.gain_q + head * kHeadDim + d0);
+    const float4 gq1 = *reinterpret_cast<const float4*>(a.gain_q + head * kHeadDim + d0 + 4);
+    const float4 gk0 = *reinterpret_cast<const float4*>(a.gain_k + head * kHeadDim + d0);
+    const float4 gk1 = *reinterpret_cast<const float4*>(a.gain_k + head * kHeadDim + d0 + 4);
+    const float gq[8] = {gq0.x, gq0.y, gq0.z, gq0.w, gq1.x, gq1.y, gq1.z, gq1.w};
+    const float gk[8] = {gk0.x, gk0.y, gk0.z, gk0.w, gk1.x, gk1.y, gk1.z, gk1.w};
+    const uint32_t* uq = reinterpret_cast<const uint32_t*>(&rq[it]);
+    const uint32_t* uk = reinterpret_cast<const uint32_t*>(&rk[it]);
+    uint32_t oq[4], ok[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const float qa = bf16_lo(uq[p]) * rq_scale[it] * gq[2 * p];
+      const float qb = bf16_hi(uq[p]) * rq_scale[it] * gq[2 * p + 1];
+      const float ka = bf16_lo(uk[p]) * rk_scale[it] * gk[2 * p];
+      const float kb = bf16_hi(uk[p]) * rk_scale[it] * gk[2 * p + 1];
+      oq[p] = pack_bf16x2(qa * cs[p] - qb * sn[p], qa * sn[p] + qb * cs[p]);
+      ok[p] = pack_bf16x2(ka * cs[p] - kb * sn[p], ka * sn[p] + kb * cs[p]);
+    }
+    *reinterpret_cast<uint4*>(a.q_out + qo_base + (int64_t)head * a.qo_head + d0) =
+        make_uint4(oq[0], oq[1], oq[2], oq[3]);
+    *reinterpret_cast<uint4*>(a.k_cache + c_base + (int64_t)head * a.c_head + d0) =
+        make_uint4(ok[0], ok[1], ok[2], ok[3]);
+  }
+}
+
+template <int ITERS>
+hipError_t launch_rope_t(const RopeArgs& a, hipStream_t st) {
+  const int blocks = (a.n_tokens + kWavesPerBlock - 1) / kWavesPerBlock;
+  hipLaunchKernelGGL(rope_kernel<ITERS>, dim3(blocks), dim3(64 * kWavesPerBlock), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+int rope_max_heads() { return 64; }
+
+hipError_t launch_build_table(const crope_table_desc& d, float* table, hipStream_t st) {
+  const TableLayout tl = table_layout(d);
+  const int64_t n = tl.total_floats / 2;
+  const int threads = 256;
+  const int blocks = (int)((n + threads - 1) / threads);
+  hipLaunchKernelGGL(build_table_kernel, dim3(blocks), dim3(threads), 0, st, table, tl, d.dim_t,
+                     d.dim_h, d.dim_w, d.theta);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope(const RopeArgs& a, hipStream_t st) {
+  const int iters = (a.n_heads + 3) / 4;
+  if (iters <= 1) return launch_rope_t<1>(a, st);
+  if (iters <= 2) return launch_rope_t<2>(a, st);
+  if (iters <= 3) return launch_rope_t<3>(a, st);
+  if (iters <= 4) return launch_rope_t<4>(a, st);
+  if (iters <= 6) return launch_rope_t<6>(a, st);
+  if (iters <= 8) return launch_rope_t<8>(a, st);
+  if (iters <= 10) return launch_rope_t<10>(a, st);
+  if (iters <= 12) return launch_rope_t<12>(a, st);
+  return launch_rope_t<16>(a, st);
+}
+
+}  // namespace crope

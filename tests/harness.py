@@ -1,0 +1,150 @@
+"""Shared test plumbing: runs one configuration through the HIP path (via the C-ABI
+binding) and through the CPU oracle on the same seeded inputs, and compares.
+
+Tolerances (bf16 outputs): max-abs <= 2e-2 and relative L2 <= 1e-2.  A bf16 number of
+magnitude >= 8 has a half-ulp of 2^-5 > 2e-2, so for tensors that can hold such values
+(rotated keys under a per-head gain scale) the element bound is 2e-2 + 2^-8*|oracle|:
+the stated absolute bound plus bf16's own worst-case rounding of the oracle value.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from paper_2603_06664_amd import workloads as W
+
+MAX_ABS = 2e-2
+REL_L2 = 1e-2
+SCALE = 128 ** -0.5
+
+
+def bits_to_f64(b: np.ndarray) -> np.ndarray:
+    return W.bf16_bits_to_f32(b).astype(np.float64)
+
+
+def errors(got: np.ndarray, ref: np.ndarray):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    diff = np.abs(got - ref)
+    max_abs = float(diff.max()) if diff.size else 0.0
+    denom = float(np.sqrt((ref ** 2).sum()))
+    rel_l2 = float(np.sqrt((diff ** 2).sum()) / denom) if denom > 0 else 0.0
+    excess = float((diff - (MAX_ABS + 2.0 ** -8 * np.abs(ref))).max()) if diff.size else -1.0
+    return max_abs, rel_l2, excess
+
+
+def assert_close(name, got, ref, strict_abs=True):
+    max_abs, rel_l2, excess = errors(got, ref)
+    msg = "%s: max_abs=%.3e rel_l2=%.3e" % (name, max_abs, rel_l2)
+    assert np.all(np.isfinite(np.asarray(got, dtype=np.float64))), msg + " (non-finite)"
+    assert rel_l2 <= REL_L2, msg
+    if strict_abs:
+        assert max_abs <= MAX_ABS, msg
+    else:
+        assert excess <= 0.0, msg + " (beyond 2e-2 + 2^-8*|ref|)"
+    return max_abs, rel_l2
+
+
+# ------------------------------------------------------------------ oracle side
+def oracle_chain(cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, q_rows=None):
+    """Returns dict with q_rot [n_q,H,D], k_cache/v_cache [cap,H,D] (fp64), segs, o, lse.
+    ``q_rows``: optional indices of query rows for which attention is evaluated."""
+    import oracle
+    H, D = cfg.n_heads, cfg.head_dim
+    group = H * D if norm_group is None else norm_group
+    cap_tokens = cfg.capacity_frames * cfg.hw
+    cache = oracle.Cache(cap_tokens, H, D)
+    kf, vf = bits_to_f64(inp.k), bits_to_f64(inp.v)
+    q_rot = None
+    for (s, nf, row0, n, off, is_cur) in W.chunk_schedule(cfg):
+        k_rot = oracle.qk_norm_rotate(kf[row0:row0 + n], inp.gain_k, cfg.eps, group, cfg.dims,
+                                      cfg.theta, cfg.grid_h, cfg.grid_w, s, off)
+        cache.write(dst_row(cfg, s, off), k_rot, vf[row0:row0 + n])
+        if is_cur:
+            q_rot = oracle.qk_norm_rotate(bits_to_f64(inp.q), inp.gain_q, cfg.eps, group, cfg.dims,
+                                          cfg.theta, cfg.grid_h, cfg.grid_w, s, off)
+    segs = visible_segments(cfg)
+    kk, vv = cache.gather(segs)
+    qs = q_rot if q_rows is None else q_rot[np.asarray(q_rows)]
+    o, lse = oracle.attention(qs, kk, vv, SCALE)
+    return dict(q_rot=q_rot, k_cache=cache.k, v_cache=cache.v, segs=segs, o=o, lse=lse)
+
+
+def dst_row(cfg: W.ChunkConfig, start_frame: int, token_offset: int) -> int:
+    """Cache row where the call for (start_frame, token_offset) writes its first token."""
+    return W.cache_slot(cfg, start_frame) * cfg.hw + token_offset
+
+
+def visible_segments(cfg: W.ChunkConfig):
+    """Row segments holding frames first_kv_frame .. start_frame+n_frames-1, oldest first,
+    merged where slots are consecutive."""
+    segs = []
+    for f in range(cfg.first_kv_frame, cfg.start_frame + cfg.n_frames):
+        start = W.cache_slot(cfg, f) * cfg.hw
+        if segs and segs[-1][0] + segs[-1][1] == start:
+            segs[-1] = (segs[-1][0], segs[-1][1] + cfg.hw)
+        else:
+            segs.append((start, cfg.hw))
+    return segs
+
+
+# ------------------------------------------------------------------ HIP side
+def to_dev_bf16(bits: np.ndarray):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def dev_bits(t) -> np.ndarray:
+    import torch
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def make_table(desc=None):
+    import torch
+    import paper_2603_06664_amd as P
+    desc = desc or P.TableDesc()
+    tab = torch.empty(P.crope_table_bytes(desc) // 4, dtype=torch.float32, device="cuda")
+    P.crope_build_table(desc, tab)
+    return desc, tab
+
+
+def hip_chain(cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, want_lse=True):
+    """Runs table build, every append call of the schedule, then attention, through the
+    C ABI.  Returns numpy results (bf16 bits widened to fp64 where noted)."""
+    import torch
+    import paper_2603_06664_amd as P
+    H, D = cfg.n_heads, cfg.head_dim
+    group = H * D if norm_group is None else norm_group
+    desc, tab = make_table(P.TableDesc(dim_t=cfg.dims[0], dim_h=cfg.dims[1], dim_w=cfg.dims[2],
+                                       theta=cfg.theta))
+    cap = cfg.capacity_frames * cfg.hw
+    k_cache = torch.zeros((cap, H, D), dtype=torch.bfloat16, device="cuda")
+    v_cache = torch.zeros_like(k_cache)
+    q = to_dev_bf16(inp.q)
+    k = to_dev_bf16(inp.k)
+    v = to_dev_bf16(inp.v)
+    gq = torch.from_numpy(inp.gain_q).cuda()
+    gk = torch.from_numpy(inp.gain_k).cuda()
+    q_out = torch.empty_like(q)
+    scratch_q = None
+    for (s, nf, row0, n, off, is_cur) in W.chunk_schedule(cfg):
+        if is_cur:
+            qi, qo = q, q_out
+        else:
+            # history / other ranks' calls: only their k, v matter; feed k as a stand-in q
+            if scratch_q is None or scratch_q.shape[0] < n:
+                scratch_q = torch.empty((n, H, D), dtype=torch.bfloat16, device="cuda")
+            qi, qo = k[row0:row0 + n], scratch_q[:n]
+        P.crope_qk_norm_rotate_append(desc, tab, qi, k[row0:row0 + n], v[row0:row0 + n], gq, gk,
+                                      cfg.eps, group, n, H, cfg.grid_h, cfg.grid_w, s, off, qo,
+                                      k_cache, v_cache, cap, dst_row(cfg, s, off))
+    segs = visible_segments(cfg)
+    out = torch.empty_like(q_out)
+    lse = torch.empty((H, cfg.n_q), dtype=torch.float32, device="cuda") if want_lse else None
+    n_keys = sum(n for _, n in segs)
+    ws_bytes = P.chunk_attention_workspace_bytes(cfg.n_q, H, n_keys)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    P.chunk_attention(q_out, cfg.n_q, H, k_cache, v_cache, cap, segs, SCALE, out, lse, ws, ws_bytes)
+    torch.cuda.synchronize()
+    return dict(q_rot=bits_to_f64(dev_bits(q_out)), k_cache=bits_to_f64(dev_bits(k_cache)),
+                v_cache_bits=dev_bits(v_cache), o=bits_to_f64(dev_bits(out)),
+                lse=lse.cpu().numpy().astype(np.float64) if want_lse else None, segs=segs)

@@ -1,0 +1,144 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2603_06664_amd as P
+from paper_2603_06664_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return B._load()
+
+
+def test_exports_every_declared_symbol(lib):
+    hdr = open(os.path.join(ROOT, "include", "crope.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b((?:crope_|chunk_attention)\w*)\s*\(", hdr))
+    assert {"crope_build_table", "crope_qk_norm_rotate_append", "chunk_attention",
+            "crope_table_bytes", "chunk_attention_workspace_bytes", "crope_last_error",
+            "crope_version"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_version_and_table_bytes():
+    assert "gfx950" in P.crope_version()
+    d = P.TableDesc()
+    assert P.crope_table_bytes(d) == 4 * 2 * (1024 * 22 + 128 * 21 + 128 * 21)
+    assert P.crope_table_bytes(P.TableDesc(head_dim=64)) == 0
+    assert P.crope_table_bytes(P.TableDesc(dim_t=43, dim_h=43)) == 0
+    assert P.crope_table_bytes(P.TableDesc(dim_t=40)) == 0          # does not sum to 128
+
+
+class _FakeTensor:
+    """Stands in for a device tensor: only the address and strides are marshalled, and the
+    calls under test must fail validation before touching memory."""
+    def __init__(self, addr, shape, strides=None, esize=2):
+        self._addr, self._shape, self._esize = addr, shape, esize
+        if strides is None:
+            strides, acc = [], 1
+            for s in reversed(shape):
+                strides.insert(0, acc)
+                acc *= s
+        self._strides = strides
+    def data_ptr(self): return self._addr
+    def dim(self): return len(self._shape)
+    def stride(self, i): return self._strides[i]
+    def numel(self):
+        n = 1
+        for s in self._shape: n *= s
+        return n
+    def element_size(self): return self._esize
+
+
+A = 0x10000  # a 16-byte aligned fake address
+
+
+def _append(desc=None, q_addr=A, n=24, H=2, gh=4, gw=6, s=5, off=0, cap=72, dst=48,
+            group=256, strides=None, tab_addr=A, heads_arg=None):
+    desc = desc or P.TableDesc()
+    t = _FakeTensor(q_addr, (n, H, 128), strides)
+    c = _FakeTensor(A, (cap, H, 128))
+    tab = _FakeTensor(tab_addr, (1,), esize=4)
+    g = _FakeTensor(A, (H * 128,), esize=4)
+    P.crope_qk_norm_rotate_append(desc, tab, t, t, t, g, g, 1e-6, group, n,
+                                  H if heads_arg is None else heads_arg, gh, gw, s, off, t, c, c,
+                                  cap, dst)
+
+
+@pytest.mark.parametrize("kwargs,code", [
+    (dict(q_addr=A + 2), B.CROPE_EALIGN),
+    (dict(strides=[2 * 128 + 4, 128, 1]), B.CROPE_EALIGN),
+    (dict(desc=P.TableDesc(head_dim=64)), B.CROPE_ESHAPE),
+    (dict(desc=P.TableDesc(max_t=5)), B.CROPE_ERANGE),          # frame 5 needs max_t >= 6
+    (dict(desc=P.TableDesc(max_w=5)), B.CROPE_ERANGE),          # grid_w 6 > 5
+    (dict(dst=49), B.CROPE_ERANGE),                             # rows 49..72 exceed capacity 72
+    (dict(dst=-1), B.CROPE_ERANGE),
+    (dict(group=64), B.CROPE_EINVAL),
+    (dict(n=-1), B.CROPE_EINVAL),
+    (dict(heads_arg=0), B.CROPE_EINVAL),
+    (dict(heads_arg=65), B.CROPE_ESHAPE),
+    (dict(gh=0), B.CROPE_EINVAL),
+    (dict(s=-1), B.CROPE_EINVAL),
+    (dict(tab_addr=0), B.CROPE_EINVAL),
+    (dict(off=24, desc=P.TableDesc(max_t=6)), B.CROPE_ERANGE),  # offset pushes rows into frame 6
+])
+def test_append_rejects_bad_arguments(kwargs, code):
+    with pytest.raises(P.CropeError) as ei:
+        _append(**kwargs)
+    assert ei.value.code == code
+    assert ei.value.message and P.crope_last_error() == ei.value.message
+
+
+def test_append_zero_tokens_is_a_noop():
+    _append(n=0, dst=72)   # valid: writes rows [72, 72)
+
+
+def _attn(n_q=24, H=2, cap=72, segs=((0, 72),), scale=128 ** -0.5, q_addr=A, ws=None, ws_bytes=0):
+    q = _FakeTensor(q_addr, (max(n_q, 1), H, 128))
+    c = _FakeTensor(A, (cap, H, 128))
+    P.chunk_attention(q, n_q, H, c, c, cap, list(segs), scale, q, None, ws, ws_bytes)
+
+
+@pytest.mark.parametrize("kwargs,code", [
+    (dict(segs=((0, 73),)), B.CROPE_ERANGE),
+    (dict(segs=((-1, 5),)), B.CROPE_ERANGE),
+    (dict(segs=((0, 0),)), B.CROPE_EINVAL),
+    (dict(segs=()), B.CROPE_EINVAL),
+    (dict(segs=((0, 1),) * 5), B.CROPE_EINVAL),
+    (dict(scale=0.0), B.CROPE_EINVAL),
+    (dict(scale=float("nan")), B.CROPE_EINVAL),
+    (dict(q_addr=A + 8), B.CROPE_EALIGN),
+    (dict(n_q=-3), B.CROPE_EINVAL),
+    (dict(H=0), B.CROPE_EINVAL),
+])
+def test_attention_rejects_bad_arguments(kwargs, code):
+    with pytest.raises(P.CropeError) as ei:
+        _attn(**kwargs)
+    assert ei.value.code == code
+
+
+def test_attention_zero_queries_is_a_noop():
+    _attn(n_q=0)
+
+
+def test_workspace_size_query():
+    assert P.chunk_attention_workspace_bytes(0, 12, 100) == 0
+    assert P.chunk_attention_workspace_bytes(4680, 12, 32760) >= 0
+
+
+def test_build_table_rejects_small_buffer():
+    d = P.TableDesc()
+    with pytest.raises(P.CropeError) as ei:
+        P.crope_build_table(d, _FakeTensor(A, (16,), esize=4))
+    assert ei.value.code == B.CROPE_EWORKSPACE
+    with pytest.raises(P.CropeError) as ei:
+        P.crope_build_table(d, _FakeTensor(A + 4, (1 << 20,), esize=4))
+    assert ei.value.code == B.CROPE_EALIGN
