@@ -2,6 +2,7 @@
 // synchronisation, no state except a thread-local error string.
 #include <cstdarg>
 #include <cstdio>
+#include <climits>
 #include "crope_internal.h"
 
 namespace {
@@ -162,17 +163,19 @@ int chunk_attention(const void* q, crope_strides q_strides, int32_t n_q, int32_t
   crope::AttnArgs a;
   a.segs.n = n_segs;
   int64_t n_keys = 0;
-  for (int i = 0; i < crope::kMaxSegments; ++i) { a.segs.start[i] = 0; a.segs.len[i] = 0; }
+  for (int i = 0; i < crope::kMaxSegments; ++i) { a.segs.end[i] = INT32_MAX; a.segs.base[i] = 0; }
   for (int i = 0; i < n_segs; ++i) {
     if (segs[i].len <= 0) return fail(CROPE_EINVAL, "segment %d has non-positive length", i);
     if (segs[i].start < 0 || segs[i].start + segs[i].len > cache_capacity_tokens)
       return fail(CROPE_ERANGE, "segment %d [%lld, %lld) lies outside the cache (capacity %lld)", i,
                   (long long)segs[i].start, (long long)(segs[i].start + segs[i].len),
                   (long long)cache_capacity_tokens);
-    a.segs.start[i] = segs[i].start; a.segs.len[i] = segs[i].len;
+    if (n_keys + segs[i].len > ((int64_t)1 << 30)) return fail(CROPE_ERANGE, "more than 2^30 visible keys");
+    a.segs.base[i] = segs[i].start - n_keys;
     n_keys += segs[i].len;
+    a.segs.end[i] = (int32_t)n_keys;
   }
-  if (n_keys > (int64_t)1 << 30) return fail(CROPE_ERANGE, "more than 2^30 visible keys");
+  for (int i = n_segs; i < crope::kMaxSegments; ++i) a.segs.base[i] = a.segs.base[n_segs - 1];
   const size_t need = crope::attention_workspace_bytes(n_q > 0 ? n_q : 1, n_heads, n_keys);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(CROPE_EWORKSPACE, "workspace has %zu bytes, needs %zu", workspace ? workspace_bytes : 0,

@@ -40,10 +40,12 @@ struct RopeArgs {
   int64_t dst_token;
 };
 
+// Visible key index vk (0 .. n_keys-1) -> cache row: row = vk + base[i] for the first i with
+// vk < end[i].  `end` are cumulative segment ends (unused entries hold INT32_MAX).
 struct Segments {
   int n;
-  int64_t start[kMaxSegments];
-  int64_t len[kMaxSegments];
+  int32_t end[kMaxSegments];
+  int64_t base[kMaxSegments];
 };
 
 struct AttnArgs {
