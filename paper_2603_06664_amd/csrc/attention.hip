@@ -14,6 +14,7 @@
 // wave's softmax (VALU) overlaps the other's MFMAs.  K and V tiles of 64 keys are copied
 // HBM -> LDS without passing through registers (global_load_lds, 16 B per lane), double
 // buffered, XOR-swizzled by choosing which global chunk each lane fetches.
+#include <type_traits>
 #include "crope_internal.h"
 
 namespace crope {
@@ -35,15 +36,6 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, h);
 }
 
-__device__ __forceinline__ int64_t key_row(const Segments& s, int vk) {
-  // visible key index -> cache row, branch-free over at most four segments
-  int64_t base = s.base[3];
-  base = vk < s.end[2] ? s.base[2] : base;
-  base = vk < s.end[1] ? s.base[1] : base;
-  base = vk < s.end[0] ? s.base[0] : base;
-  return base + vk;
-}
-
 // max over both halves of the wave (lane l and lane l^32), result in every lane
 __device__ __forceinline__ float max_across_halves(float x) {
   const u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -58,7 +50,6 @@ constexpr int BM = 128;                 // queries per work-group: 4 waves x 32
 constexpr int BN = 64;                  // keys per tile
 constexpr int kRowBytes = kHeadDim * 2; // 256 B per key row in LDS (swizzled, unpadded)
 constexpr int kTileBytes = BN * kRowBytes;   // 16 KB
-constexpr int kBufBytes = 2 * kTileBytes;    // K tile + V tile
 constexpr float kLog2e = 1.44269504088896340736f;
 // A query's reference maximum is only raised when a tile's maximum exceeds it by more than
 // this many powers of two; until then probabilities may exceed 1 (at most 2^8), which fp32
@@ -72,9 +63,193 @@ struct SplitInfo {
 
 // LDS layout of one K tile: row r (key), 16-byte chunk c (8 channels) at r*256 + ((c ^ (r&15))*16).
 // LDS layout of one V tile: row r, 32-byte pair slot p (16 channels) at r*256 + ((p ^ (r&3))*32).
+//
+// Software pipeline over 32-key blocks b (two per tile).  Sub-iteration b issues, as
+// independent instruction streams the hardware can overlap inside one wave,
+//   MFMA:  S_{b+1} = K_{b+1} . Q^T          and   O^T += V_{b-1}^T . P_{b-1}^T
+//   VALU:  P_b = exp2(S_b * c - m_ref * c)  (row sums via bf16 dot products)
+// so K is needed one block ahead of V: tile T+1's K and tile T's V are live together, and
+// the four 16 KB LDS buffers hold K_{T+1}, K_{T+2} (arriving), V_T, V_{T+1} (arriving).
+struct PipeState {
+  f32x16_t o_acc[4];
+  f32x16_t s_cur;      // raw scores of the block whose softmax is due
+  f32x16_t s_init;     // accumulator seed of the next S block: 0, or -inf for keys past the end
+  uint32_t p_prev[8];  // bf16 probabilities of the block whose P.V is due
+  float m_ref, mc, l_run;
+};
+
+// key0_next: global index of the first key of the block whose scores this call computes.
+template <bool DO_S, bool DO_PV, bool DO_SOFTMAX>
+__device__ __forceinline__ void sub_iteration(PipeState& st, const bf16x8_t (&qf)[8],
+                                              const uint8_t* k_half,   // K rows of block b+1
+                                              const uint8_t* v_half,   // V rows of block b-1
+                                              const int (&k_off)[8], const int (&v_off)[4],
+                                              int key0_next, int n_keys, int g, float c, float tau) {
+  // ---- rare events, decided wave-uniformly: the reference maximum must be raised, or the
+  // block about to be scored reaches beyond the last visible key
+  bool raise = false;
+  float mx = 0.f;
+  if (DO_SOFTMAX) {
+    mx = fmaxf(fmaxf(st.s_cur[0], st.s_cur[1]), st.s_cur[2]);
+#pragma unroll
+    for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, st.s_cur[i]), st.s_cur[i + 1]);
+    mx = fmaxf(mx, st.s_cur[15]);
+    mx = max_across_halves(mx);
+    raise = mx > st.m_ref + tau;   // always true for the first block (m_ref = -inf)
+  }
+  const bool tail_next = DO_S && (key0_next + 32 > n_keys);
+  if (__builtin_amdgcn_ballot_w64(raise) != 0 || tail_next) {
+    if (DO_SOFTMAX) {
+      const float m_new = raise ? mx : st.m_ref;
+      const float alpha = __builtin_amdgcn_exp2f((st.m_ref - m_new) * c);   // 1 where unchanged
+      st.m_ref = m_new;
+      st.mc = m_new * c;
+      st.l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st.o_acc[db][i] *= alpha;
+      if (DO_PV) {
+        // the pending probabilities were formed against the old reference
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          st.p_prev[i] = pack_bf16x2(__uint_as_float(st.p_prev[i] << 16) * alpha,
+                                     __uint_as_float(st.p_prev[i] & 0xffff0000u) * alpha);
+      }
+    }
+    if (DO_S) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        st.s_init[i] = (key0_next + 8 * (i >> 2) + 4 * g + (i & 3) >= n_keys) ? -INFINITY : 0.f;
+    }
+  }
+  // ---- the overlapped part: one scheduling region whose instruction mix is pinned below
+  f32x16_t s_new = st.s_init;
+  uint32_t p_new[8];
+  const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
+  bf16x8_t pb[2];
+  if (DO_PV) {
+    pb[0] = __builtin_bit_cast(bf16x8_t, make_uint4(st.p_prev[0], st.p_prev[1], st.p_prev[2], st.p_prev[3]));
+    pb[1] = __builtin_bit_cast(bf16x8_t, make_uint4(st.p_prev[4], st.p_prev[5], st.p_prev[6], st.p_prev[7]));
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (DO_S) {
+      const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(k_half + k_off[i]));
+      s_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[i], s_new, 0, 0, 0);
+    }
+    if (DO_PV) {
+      const int jj = i >> 2, db = i & 3;
+      const uint8_t* vp = v_half + v_off[db] + jj * 16 * kRowBytes;
+      const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(vp));
+      const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) s16x4_t*)(vp + 8 * kRowBytes));
+      const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
+      const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
+      st.o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[jj], st.o_acc[db], 0, 0, 0);
+    }
+    if (DO_SOFTMAX) {
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(st.s_cur[2 * i], c, -st.mc));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(st.s_cur[2 * i + 1], c, -st.mc));
+      const uint32_t u = pack_bf16x2(p0, p1);
+      p_new[i] = u;
+      // denominator from the rounded values the MFMA will see
+      st.l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, st.l_run, false);
+    }
+  }
+  // Issue order: fragment reads run two steps ahead; every MFMA is followed by a few VALU /
+  // transcendental instructions of the (independent) softmax stream so that the matrix pipe
+  // and the vector ALU are busy at the same time inside this wave.
+  if (DO_S && DO_PV && DO_SOFTMAX) {
+    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);     // DS reads for steps 0 and 1
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // VALU  (2 fma)
+      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // TRANS (2 exp)
+      if (i < 6) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // DS reads for step i+2
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // VALU  (cvt, dot2, address)
+    }
+  }
+  if (DO_SOFTMAX) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      // keep the softmax stream inside this scheduling region (it would otherwise be sunk
+      // to its first use in the next sub-iteration)
+      asm volatile("" : "+v"(p_new[i]));
+      st.p_prev[i] = p_new[i];
+    }
+    asm volatile("" : "+v"(st.l_run));
+  }
+  if (DO_S) st.s_cur = s_new;
+}
+
+// Per-lane constants of the HBM -> LDS tile copy.  Lane i of load instruction t moves one
+// 16-byte chunk of tile row 16*wave + 4*t + i/16 into LDS position (that row, chunk i%16);
+// which global chunk it fetches implements the swizzle.
+struct LoaderChunks {
+  int k[4], v[4];   // element offset of the chunk this lane fetches, per load instruction t
+};
+struct Loader {     // scalars only, so that it is promoted to registers at once
+  const uint16_t *k_head, *v_head;   // cache base of this head
+  int seg_end0, seg_end1, seg_end2;     // visible key index -> cache row: vk + base of its segment
+  int seg_base3, d2, d1, d0;            // base3, base2-base3, base1-base2, base0-base1
+  int64_t c_tok;
+  int row0;       // 16*wave + lane/16
+  int lds_row0;   // 16*wave
+  int key_first;  // first visible key of this work-group's split
+  int n_keys;
+};
+
+template <bool IS_V>
+__device__ __forceinline__ void load_tile(const Loader& L, const LoaderChunks& ch, int tile, uint8_t* dst_tile) {
+  uint8_t* dst = dst_tile + L.lds_row0 * kRowBytes;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    int vk = L.key_first + tile * BN + L.row0 + 4 * t;
+    vk = min(vk, L.n_keys - 1);   // tail rows re-read the last key; their scores are masked
+    // arithmetic select (no value select the compiler could turn into a table lookup)
+    const int row = vk + L.seg_base3 + (vk < L.seg_end2 ? L.d2 : 0) + (vk < L.seg_end1 ? L.d1 : 0) +
+                    (vk < L.seg_end0 ? L.d0 : 0);
+    const int64_t off = (int64_t)row * L.c_tok;
+    const uint16_t* src = IS_V ? L.v_head + off + ch.v[t] : L.k_head + off + ch.k[t];
+    __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(dst + t * 4 * kRowBytes), 16, 0, 0);
+  }
+}
+
+struct FragOffsets {
+  int k_off[8];
+  int v_off[4];
+};
+
+// Iteration T: wait for K of tile T+1 and V of tile T, start the copies of K_{T+2} and V_{T+1}
+// into the two buffers nobody reads any more, then run the two 32-key sub-iterations.
+__device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, const LoaderChunks& ch,
+                                               const bf16x8_t (&qf)[8],
+                                               const FragOffsets& fo, int T, int n_t, uint8_t* k_load,
+                                               uint8_t* v_load, const uint8_t* k_read, const uint8_t* v_read,
+                                               int g, float c, float tau) {
+  constexpr int kHalf = 32 * kRowBytes;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();   // K_{T+1}, V_T have landed; every wave is done with K_T and V_{T-1}
+  if (T + 2 < n_t) load_tile<false>(L, ch, T + 2, k_load);
+  load_tile<true>(L, ch, T + 1, v_load);
+  sub_iteration<true, true, true>(st, qf, k_read, v_read, fo.k_off, fo.v_off, L.key_first + (2 * T + 2) * 32,
+                                  L.n_keys, g, c, tau);
+  sub_iteration<true, true, true>(st, qf, k_read + kHalf, v_read + kHalf, fo.k_off, fo.v_off,
+                                  L.key_first + (2 * T + 3) * 32, L.n_keys, g, c, tau);
+}
+
 __global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
 void attention_kernel(AttnArgs a, SplitInfo sp) {
-  __shared__ __attribute__((aligned(1024))) uint8_t lds[2 * kBufBytes];
+  // Four separate LDS objects (not one array): the compiler can then prove that the
+  // fragment reads of one buffer do not alias the in-flight HBM->LDS copies into another,
+  // and does not make the reads wait for the prefetch.
+  __shared__ __attribute__((aligned(1024))) uint8_t k_lds0[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t k_lds1[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t v_lds0[kTileBytes];
+  __shared__ __attribute__((aligned(1024))) uint8_t v_lds1[kTileBytes];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -84,38 +259,38 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   const int head = blockIdx.y;
   const int split = blockIdx.z;
   const int q0 = blockIdx.x * BM + wave * 32;
+  const int n_keys = (int)a.n_keys;
 
-  const int n_tiles_total = (int)((a.n_keys + BN - 1) / BN);
+  const int n_tiles_total = (n_keys + BN - 1) / BN;
   const int tile_begin = split * sp.tiles_per_split;
-  const int tile_end = min(n_tiles_total, tile_begin + sp.tiles_per_split);
+  const int n_t = min(n_tiles_total, tile_begin + sp.tiles_per_split) - tile_begin;   // >= 1
 
-  // ---- loader constants: lane i of load instruction t moves one 16-byte chunk of tile row
-  // 16*wave + 4*t + i/16 into LDS position (that row, chunk i%16)
-  const int l_row = lane >> 4, l_chunk = lane & 15;
-  int k_src_chunk[4], v_src_chunk[4];
-#pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    const int row = 16 * wave + 4 * t + l_row;
-    k_src_chunk[t] = (l_chunk ^ (row & 15)) * 8;                               // elements
-    v_src_chunk[t] = ((((l_chunk >> 1) ^ (row & 3)) << 1) | (l_chunk & 1)) * 8;
-  }
-  const uint16_t* kc_head = a.k_cache + (int64_t)head * a.c_head;
-  const uint16_t* vc_head = a.v_cache + (int64_t)head * a.c_head;
-
-  auto issue_tile_loads = [&](int kt, int buf) {
-    uint8_t* kdst = lds + buf * kBufBytes + (16 * wave) * kRowBytes;
-    uint8_t* vdst = kdst + kTileBytes;
+  Loader L;
+  LoaderChunks ch;
+  {
+    const int l_row = lane >> 4, l_chunk = lane & 15;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      int vk = kt * BN + 16 * wave + 4 * t + l_row;
-      vk = min(vk, (int)a.n_keys - 1);   // tail rows re-read the last key; their scores are masked
-      const int64_t off = key_row(a.segs, vk) * a.c_tok;
-      __builtin_amdgcn_global_load_lds(GLB_PTR(kc_head + off + k_src_chunk[t]),
-                                       LDS_PTR(kdst + t * 4 * kRowBytes), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(GLB_PTR(vc_head + off + v_src_chunk[t]),
-                                       LDS_PTR(vdst + t * 4 * kRowBytes), 16, 0, 0);
+      const int row = 16 * wave + 4 * t + l_row;
+      ch.k[t] = (l_chunk ^ (row & 15)) * 8;
+      ch.v[t] = ((((l_chunk >> 1) ^ (row & 3)) << 1) | (l_chunk & 1)) * 8;
     }
-  };
+    L.k_head = a.k_cache + (int64_t)head * a.c_head;
+    L.v_head = a.v_cache + (int64_t)head * a.c_head;
+    // through readfirstlane: plain scalar values, not addresses the compiler may select between
+    L.seg_end0 = __builtin_amdgcn_readfirstlane(a.segs.end[0]);
+    L.seg_end1 = __builtin_amdgcn_readfirstlane(a.segs.end[1]);
+    L.seg_end2 = __builtin_amdgcn_readfirstlane(a.segs.end[2]);
+    L.seg_base3 = __builtin_amdgcn_readfirstlane(a.segs.base[3]);
+    L.d2 = __builtin_amdgcn_readfirstlane(a.segs.base[2] - a.segs.base[3]);
+    L.d1 = __builtin_amdgcn_readfirstlane(a.segs.base[1] - a.segs.base[2]);
+    L.d0 = __builtin_amdgcn_readfirstlane(a.segs.base[0] - a.segs.base[1]);
+    L.c_tok = a.c_tok;
+    L.row0 = 16 * wave + l_row;
+    L.lds_row0 = 16 * wave;
+    L.key_first = tile_begin * BN;
+    L.n_keys = n_keys;
+  }
 
   // ---- Q^T fragments (B operand): lane holds query n, channels 16*ks + 8g .. +7
   bf16x8_t qf[8];
@@ -128,117 +303,77 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
       qf[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(qp + 16 * ks));
   }
 
-  // ---- fragment read offsets (bytes inside a buffer)
-  // K: row kb*32 + n, logical chunk 2*ks + g  ->  (2*ks) ^ (g ^ (n&15)) after the swizzle
-  int k_off[8];
+  // ---- fragment read offsets (bytes inside a 32-key half tile)
+  // K: row n, logical chunk 2*ks + g  ->  (2*ks) ^ (g ^ (n&15)) after the swizzle
+  FragOffsets fo;
+  int (&k_off)[8] = fo.k_off;
+  int (&v_off)[4] = fo.v_off;
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * kRowBytes + (((2 * ks + g) ^ (n & 15)) << 4);
   // V (transposing read): 16-lane group G = lane/16 covers channel half mh = G&1 of key half g;
   // lane i of the group points at row 4g + i/4 (+ step offset), channels 16*(db + 4*mh) + 4*(i%4)
-  int v_off[4];
   {
     const int i16 = lane & 15, mh = (lane >> 4) & 1;
     const int kk = i16 >> 2, cc = i16 & 3;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
-      v_off[db] = kTileBytes + (4 * g + kk) * kRowBytes + (((db ^ kk) + 4 * mh) << 5) + cc * 8;
+      v_off[db] = (4 * g + kk) * kRowBytes + (((db ^ kk) + 4 * mh) << 5) + cc * 8;
   }
 
-  f32x16_t o_acc[4];
+  PipeState st;
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) o_acc[db][i] = 0.f;
+    for (int i = 0; i < 16; ++i) st.o_acc[db][i] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) st.s_init[i] = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) st.p_prev[i] = 0u;
   const float c = a.scale * kLog2e;   // exp(x*scale) = exp2(x*c)
   const float tau = kRescaleLog2 / c; // in raw score units
-  float m_ref = -INFINITY;            // reference maximum of raw scores of query n
-  float mc = 0.f;                     // m_ref * c
-  float l_run = 0.f;                  // this lane's share of the denominator
+  st.m_ref = -INFINITY;               // reference maximum of raw scores of query n
+  st.mc = 0.f;                        // m_ref * c
+  st.l_run = 0.f;                     // this lane's share of the denominator
+  const int key_base = tile_begin * BN;
+  constexpr int kHalf = 32 * kRowBytes;
 
-  if (tile_begin < tile_end) issue_tile_loads(tile_begin, 0);
-
-  for (int kt = tile_begin; kt < tile_end; ++kt) {
-    const int buf = (kt - tile_begin) & 1;
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();   // tile kt has landed for every wave; everyone is done with buffer buf^1
-    if (kt + 1 < tile_end) issue_tile_loads(kt + 1, buf ^ 1);
-    const uint8_t* base = lds + buf * kBufBytes;
-
-    // ---- S^T = K . Q^T : two independent 32-key accumulators, interleaved
-    f32x16_t s_acc[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s_acc[kb][i] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const bf16x8_t kf = __builtin_bit_cast(
-            bf16x8_t, *reinterpret_cast<const uint4*>(base + k_off[ks] + kb * 32 * kRowBytes));
-        s_acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s_acc[kb], 0, 0, 0);
-      }
-    }
-    // accumulator element i of block kb: key kt*BN + kb*32 + 8*(i/4) + 4*g + (i%4), query n
-    if (kt == n_tiles_total - 1) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int vk = kt * BN + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-          if (vk >= (int)a.n_keys) s_acc[kb][i] = -INFINITY;
-        }
-    }
-    // ---- online softmax for query n
-    float mx = fmaxf(s_acc[0][0], s_acc[1][0]);
-#pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, fmaxf(s_acc[0][i], s_acc[1][i]));
-    mx = max_across_halves(mx);
-    const bool raise = mx > m_ref + tau;   // always true on the first tile (m_ref = -inf)
-    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-      const float m_new = raise ? mx : m_ref;
-      const float alpha = __builtin_amdgcn_exp2f((m_ref - m_new) * c);   // 1 where unchanged, 0 at start
-      m_ref = m_new;
-      mc = m_new * c;
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
-    }
-    uint32_t pf[2][8];
-    const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][i], c, -mc));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][i + 1], c, -mc));
-        const uint32_t u = pack_bf16x2(p0, p1);
-        pf[kb][i >> 1] = u;
-        // denominator from the rounded values the MFMA sees
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, l_run, false);
-      }
-
-    // ---- O^T += V^T . P^T : 4 steps of 16 keys x 4 channel blocks
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int kb = j >> 1, jj = j & 1;
-      const uint4 pu = make_uint4(pf[kb][4 * jj], pf[kb][4 * jj + 1], pf[kb][4 * jj + 2], pf[kb][4 * jj + 3]);
-      const bf16x8_t pb = __builtin_bit_cast(bf16x8_t, pu);
-      const int step_off = (kb * 32 + 16 * jj) * kRowBytes;
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4_t*)(base + v_off[db] + step_off));
-        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4_t*)(base + v_off[db] + step_off + 8 * kRowBytes));
-        const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
-        const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
-        o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb, o_acc[db], 0, 0, 0);
-      }
-    }
+  // ---- prologue: S_0 and S_1 from tile 0, P_0
+  load_tile<false>(L, ch, 0, k_lds0);
+  load_tile<true>(L, ch, 0, v_lds0);
+  if (n_t > 1) load_tile<false>(L, ch, 1, k_lds1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  {
+    st.s_cur = st.s_init;   // zeros; replaced by S_0 below
+    sub_iteration<true, false, false>(st, qf, k_lds0, nullptr, k_off, v_off, key_base, n_keys, g, c, tau);
+    const f32x16_t s0 = st.s_cur;
+    sub_iteration<true, false, false>(st, qf, k_lds0 + kHalf, nullptr, k_off, v_off, key_base + 32, n_keys, g, c, tau);
+    const f32x16_t s1 = st.s_cur;
+    st.s_cur = s0;
+    sub_iteration<false, false, true>(st, qf, nullptr, nullptr, k_off, v_off, 0, n_keys, g, c, tau);   // P_0
+    st.s_cur = s1;
   }
+
+  // ---- steady state: iteration T scores tile T+1 (K) and accumulates tile T (V)
+  int T = 0;
+  for (; T + 2 < n_t; T += 2) {
+    tile_iteration(st, L, ch, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);       // even T
+    tile_iteration(st, L, ch, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g, c, tau);   // odd T
+  }
+  if (T + 1 < n_t) {
+    tile_iteration(st, L, ch, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);
+    ++T;
+  }
+  // ---- drain: T == n_t - 1; last tile's V, last block's softmax
+  {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const uint8_t* vb = (T & 1) ? v_lds1 : v_lds0;
+    sub_iteration<false, true, true>(st, qf, nullptr, vb, k_off, v_off, 0, n_keys, g, c, tau);
+    sub_iteration<false, true, false>(st, qf, nullptr, vb + kHalf, k_off, v_off, 0, n_keys, g, c, tau);
+  }
+  f32x16_t* o_acc = st.o_acc;
+  const float m_ref = st.m_ref, l_run = st.l_run;
 
   // ---- epilogue.  O^T block db, element i: channel 16*db + 64*(i/8) + 8*((i/4)&1) + 4*g + (i%4)
   const float l_tot = sum_across_halves(l_run);

@@ -160,6 +160,7 @@ int chunk_attention(const void* q, crope_strides q_strides, int32_t n_q, int32_t
       !stride_ok(out_strides.token) || !stride_ok(out_strides.head))
     return fail(CROPE_EALIGN, "strides must be positive multiples of 8 elements");
   if (cache_capacity_tokens <= 0) return fail(CROPE_EINVAL, "cache capacity must be positive");
+  if (cache_capacity_tokens > INT32_MAX) return fail(CROPE_ERANGE, "cache capacity above 2^31-1 rows");
   crope::AttnArgs a;
   a.segs.n = n_segs;
   int64_t n_keys = 0;
@@ -171,7 +172,7 @@ int chunk_attention(const void* q, crope_strides q_strides, int32_t n_q, int32_t
                   (long long)segs[i].start, (long long)(segs[i].start + segs[i].len),
                   (long long)cache_capacity_tokens);
     if (n_keys + segs[i].len > ((int64_t)1 << 30)) return fail(CROPE_ERANGE, "more than 2^30 visible keys");
-    a.segs.base[i] = segs[i].start - n_keys;
+    a.segs.base[i] = (int32_t)(segs[i].start - n_keys);
     n_keys += segs[i].len;
     a.segs.end[i] = (int32_t)n_keys;
   }

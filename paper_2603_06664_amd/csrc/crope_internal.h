@@ -45,7 +45,7 @@ struct RopeArgs {
 struct Segments {
   int n;
   int32_t end[kMaxSegments];
-  int64_t base[kMaxSegments];
+  int32_t base[kMaxSegments];   // cache rows are below 2^31
 };
 
 struct AttnArgs {
