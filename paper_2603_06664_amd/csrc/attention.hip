@@ -14,6 +14,7 @@
 // wave's softmax (VALU) overlaps the other's MFMAs.  K and V tiles of 64 keys are copied
 // HBM -> LDS without passing through registers (global_load_lds, 16 B per lane), double
 // buffered, XOR-swizzled by choosing which global chunk each lane fetches.
+#include <cstdlib>
 #include <type_traits>
 #include "crope_internal.h"
 
@@ -185,36 +186,56 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const bf16x8_t (&qf
   if (DO_S) st.s_cur = s_new;
 }
 
-// Per-lane constants of the HBM -> LDS tile copy.  Lane i of load instruction t moves one
-// 16-byte chunk of tile row 16*wave + 4*t + i/16 into LDS position (that row, chunk i%16);
-// which global chunk it fetches implements the swizzle.
-struct LoaderChunks {
-  int k[4], v[4];   // element offset of the chunk this lane fetches, per load instruction t
+// HBM -> LDS tile copy.  Lane i of load instruction t moves one 16-byte chunk of tile row
+// 16*wave + 4*t + i/16 into LDS position (that row, chunk i%16); which global chunk it
+// fetches implements the swizzle.  A tile whose 64 keys are consecutive cache rows (the
+// common case) is addressed as a wave-uniform base plus a per-lane byte offset that never
+// changes, so the steady state spends no vector instructions on addresses.
+struct LoaderOffsets {
+  uint32_t k[4], v[4];   // byte offset of this lane's chunk from the tile's first row, per t
 };
 struct Loader {     // scalars only, so that it is promoted to registers at once
-  const uint16_t *k_head, *v_head;   // cache base of this head
-  int seg_end0, seg_end1, seg_end2;     // visible key index -> cache row: vk + base of its segment
-  int seg_base3, d2, d1, d0;            // base3, base2-base3, base1-base2, base0-base1
-  int64_t c_tok;
+  const uint8_t *k_head, *v_head;    // cache base of this head (bytes)
+  int seg_end0, seg_end1, seg_end2;  // visible key index -> cache row: vk + base of its segment
+  int seg_base3, d2, d1, d0;         // base3, base2-base3, base1-base2, base0-base1
+  int64_t row_bytes;                 // c_tok * 2
   int row0;       // 16*wave + lane/16
   int lds_row0;   // 16*wave
   int key_first;  // first visible key of this work-group's split
   int n_keys;
+  uint32_t k_chunk_bytes[4], v_chunk_bytes[4];   // swizzled chunk offset inside a row (slow path)
 };
 
+__device__ __forceinline__ int seg_row(const Loader& L, int vk) {
+  // arithmetic select (no value select the compiler could turn into a table lookup)
+  return vk + L.seg_base3 + (vk < L.seg_end2 ? L.d2 : 0) + (vk < L.seg_end1 ? L.d1 : 0) +
+         (vk < L.seg_end0 ? L.d0 : 0);
+}
+
 template <bool IS_V>
-__device__ __forceinline__ void load_tile(const Loader& L, const LoaderChunks& ch, int tile, uint8_t* dst_tile) {
+__device__ __forceinline__ void load_tile(const Loader& L, const LoaderOffsets& lo, int tile, uint8_t* dst_tile) {
   uint8_t* dst = dst_tile + L.lds_row0 * kRowBytes;
+  const int k_first = L.key_first + tile * BN;   // wave-uniform
+  const int k_last = k_first + BN - 1;
+  const uint8_t* head = IS_V ? L.v_head : L.k_head;
+  const int r_first = seg_row(L, k_first);
+  if (k_last < L.n_keys && seg_row(L, k_last) - r_first == BN - 1) {
+    // 64 consecutive cache rows: uniform base + constant per-lane offset
+    const uint8_t* base = head + (int64_t)r_first * L.row_bytes;
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
-    int vk = L.key_first + tile * BN + L.row0 + 4 * t;
-    vk = min(vk, L.n_keys - 1);   // tail rows re-read the last key; their scores are masked
-    // arithmetic select (no value select the compiler could turn into a table lookup)
-    const int row = vk + L.seg_base3 + (vk < L.seg_end2 ? L.d2 : 0) + (vk < L.seg_end1 ? L.d1 : 0) +
-                    (vk < L.seg_end0 ? L.d0 : 0);
-    const int64_t off = (int64_t)row * L.c_tok;
-    const uint16_t* src = IS_V ? L.v_head + off + ch.v[t] : L.k_head + off + ch.k[t];
-    __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(dst + t * 4 * kRowBytes), 16, 0, 0);
+    for (int t = 0; t < 4; ++t)
+      __builtin_amdgcn_global_load_lds(GLB_PTR(base + (IS_V ? lo.v[t] : lo.k[t])),
+                                       LDS_PTR(dst + t * 4 * kRowBytes), 16, 0, 0);
+  } else {
+    // tile straddles a segment boundary or the end of the keys: per-lane row lookup; rows
+    // past the end re-read the last key (their scores are masked)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int vk = min(k_first + L.row0 + 4 * t, L.n_keys - 1);
+      const uint8_t* src = head + (int64_t)seg_row(L, vk) * L.row_bytes +
+                           (IS_V ? L.v_chunk_bytes[t] : L.k_chunk_bytes[t]);
+      __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(dst + t * 4 * kRowBytes), 16, 0, 0);
+    }
   }
 }
 
@@ -225,7 +246,7 @@ struct FragOffsets {
 
 // Iteration T: wait for K of tile T+1 and V of tile T, start the copies of K_{T+2} and V_{T+1}
 // into the two buffers nobody reads any more, then run the two 32-key sub-iterations.
-__device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, const LoaderChunks& ch,
+__device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, const LoaderOffsets& ch,
                                                const bf16x8_t (&qf)[8],
                                                const FragOffsets& fo, int T, int n_t, uint8_t* k_load,
                                                uint8_t* v_load, const uint8_t* k_read, const uint8_t* v_read,
@@ -253,7 +274,7 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int n = lane & 31;   // query column inside the wave's 32
   const int g = lane >> 5;   // which half of each 8-key group this lane holds
   const int head = blockIdx.y;
@@ -266,17 +287,20 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   const int n_t = min(n_tiles_total, tile_begin + sp.tiles_per_split) - tile_begin;   // >= 1
 
   Loader L;
-  LoaderChunks ch;
+  LoaderOffsets ch;
   {
     const int l_row = lane >> 4, l_chunk = lane & 15;
+    L.row_bytes = a.c_tok * 2;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const int row = 16 * wave + 4 * t + l_row;
-      ch.k[t] = (l_chunk ^ (row & 15)) * 8;
-      ch.v[t] = ((((l_chunk >> 1) ^ (row & 3)) << 1) | (l_chunk & 1)) * 8;
+      L.k_chunk_bytes[t] = (l_chunk ^ (row & 15)) * 16;
+      L.v_chunk_bytes[t] = ((((l_chunk >> 1) ^ (row & 3)) << 1) | (l_chunk & 1)) * 16;
+      ch.k[t] = (uint32_t)(row * L.row_bytes) + L.k_chunk_bytes[t];
+      ch.v[t] = (uint32_t)(row * L.row_bytes) + L.v_chunk_bytes[t];
     }
-    L.k_head = a.k_cache + (int64_t)head * a.c_head;
-    L.v_head = a.v_cache + (int64_t)head * a.c_head;
+    L.k_head = reinterpret_cast<const uint8_t*>(a.k_cache + (int64_t)head * a.c_head);
+    L.v_head = reinterpret_cast<const uint8_t*>(a.v_cache + (int64_t)head * a.c_head);
     // through readfirstlane: plain scalar values, not addresses the compiler may select between
     L.seg_end0 = __builtin_amdgcn_readfirstlane(a.segs.end[0]);
     L.seg_end1 = __builtin_amdgcn_readfirstlane(a.segs.end[1]);
@@ -285,7 +309,6 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
     L.d2 = __builtin_amdgcn_readfirstlane(a.segs.base[2] - a.segs.base[3]);
     L.d1 = __builtin_amdgcn_readfirstlane(a.segs.base[1] - a.segs.base[2]);
     L.d0 = __builtin_amdgcn_readfirstlane(a.segs.base[0] - a.segs.base[1]);
-    L.c_tok = a.c_tok;
     L.row0 = 16 * wave + l_row;
     L.lds_row0 = 16 * wave;
     L.key_first = tile_begin * BN;
@@ -453,6 +476,14 @@ constexpr int kMaxSplits = 16;
 // chip's work-group slots; every split costs a partial-result round trip, so a split must
 // pay for itself.
 int choose_splits(int n_q, int n_heads, int64_t n_keys) {
+  // CROPE_ATTN_SPLITS=<n> pins the number of key splits (tuning aid); unset or 0 = automatic
+  static const int forced = [] { const char* e = getenv("CROPE_ATTN_SPLITS"); return e ? atoi(e) : 0; }();
+  const int n_tiles_all = (int)((n_keys + BN - 1) / BN);
+  if (forced > 0) {
+    int s = forced < kMaxSplits ? forced : kMaxSplits;
+    while (s > 1 && (int64_t)(s - 1) * ((n_tiles_all + s - 1) / s) >= n_tiles_all) --s;   // no empty split
+    return s;
+  }
   const int64_t units = (int64_t)((n_q + BM - 1) / BM) * n_heads;
   const int n_tiles = (int)((n_keys + BN - 1) / BN);
   int best = 1;

@@ -161,6 +161,7 @@ int chunk_attention(const void* q, crope_strides q_strides, int32_t n_q, int32_t
     return fail(CROPE_EALIGN, "strides must be positive multiples of 8 elements");
   if (cache_capacity_tokens <= 0) return fail(CROPE_EINVAL, "cache capacity must be positive");
   if (cache_capacity_tokens > INT32_MAX) return fail(CROPE_ERANGE, "cache capacity above 2^31-1 rows");
+  if (cache_strides.token > (1 << 24)) return fail(CROPE_ERANGE, "cache token stride above 2^24 elements");
   crope::AttnArgs a;
   a.segs.n = n_segs;
   int64_t n_keys = 0;
