@@ -21,6 +21,13 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+# HBM bytes per launch at workload C4 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
+# by what the same counter reads for a 1 GiB copy (x2.000 and x1.000); the summary with the
+# commands is profiles/chunk_attention_and_rope_C4_pmc.md.  Other workloads report null.
+MEASURED_TRAFFIC_BYTES = {
+    "C4": {"chunk_attention": (837675.7 * 2.000 + 14040.3 * 1.000) * 1024,
+           "crope_qk_norm_rotate_append": (21216.8 * 2.000 + 42120.0 * 1.000) * 1024},
+}
 
 
 def parse():
@@ -30,7 +37,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=256,
+    ap.add_argument("--cpu-rows", type=int, default=1024,
                     help="query rows of the workload the CPU oracle is timed on")
     ap.add_argument("--input-sets", type=int, default=8,
                     help="disjoint q/k/v input sets rotated between steps so the append kernel "
@@ -140,10 +147,14 @@ def main():
         "rope_gbps": round(rope_gbps, 1),
         "roofline": {"kernel": "chunk_attention", "bound": "mfma", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("chunk_attention"),
+                     "algorithmic_flops_per_launch": flops},
         "roofline_rope": {"kernel": "crope_qk_norm_rotate_append", "bound": "hbm",
                           "achieved": round(rope_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                          "frac": round(rope_gbps / PEAK_HBM_GBPS, 4), "traffic": None},
+                          "frac": round(rope_gbps / PEAK_HBM_GBPS, 4),
+                          "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("crope_qk_norm_rotate_append"),
+                          "algorithmic_bytes_per_launch": rope_bytes},
     }
 
     if not args.no_cpu_baseline:

@@ -493,7 +493,13 @@ int choose_splits(int n_q, int n_heads, int64_t n_keys) {
     if ((int64_t)(s - 1) * tiles_per >= n_tiles) continue;   // would leave an empty split
     const double rounds = (double)((units * s + kSlots - 1) / kSlots);
     double cost = rounds * tiles_per;                         // key tiles on the critical path
-    if (s > 1) cost += 2.0 + 0.03 * n_tiles * s / 16.0;       // partial write + combine pass
+    if (s > 1) {
+      // fp32 partials are written and read back once: (128+2)*4 B per query, head and split,
+      // at ~4 TB/s, in units of one key tile of one work-group (~2 us); a split must also
+      // win by a clear margin
+      cost += 2.0 + (double)s * n_q * n_heads * 1040.0 / 8.4e6;
+      cost *= 1.05;
+    }
     if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
   }
   return best;
