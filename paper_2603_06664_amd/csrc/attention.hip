@@ -47,7 +47,6 @@ __device__ __forceinline__ float sum_across_halves(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-constexpr int BM = 128;                 // queries per work-group: 4 waves x 32
 constexpr int BN = 64;                  // keys per tile
 constexpr int kRowBytes = kHeadDim * 2; // 256 B per key row in LDS (swizzled, unpadded)
 constexpr int kTileBytes = BN * kRowBytes;   // 16 KB
@@ -60,7 +59,11 @@ constexpr float kRescaleLog2 = 8.0f;
 struct SplitInfo {
   int n_splits;
   int tiles_per_split;
+  int q_tiles;        // ceil(n_q / (32 * waves per work-group))
+  int total_units;    // q_tiles * n_heads * n_splits
+  int units_per_xcd;  // ceil(total_units / 8)
 };
+constexpr int kXcds = 8;
 
 // LDS layout of one K tile: row r (key), 16-byte chunk c (8 channels) at r*256 + ((c ^ (r&15))*16).
 // LDS layout of one V tile: row r, 32-byte pair slot p (16 channels) at r*256 + ((p ^ (r&3))*32).
@@ -186,8 +189,9 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const bf16x8_t (&qf
   if (DO_S) st.s_cur = s_new;
 }
 
-// HBM -> LDS tile copy.  Lane i of load instruction t moves one 16-byte chunk of tile row
-// 16*wave + 4*t + i/16 into LDS position (that row, chunk i%16); which global chunk it
+// HBM -> LDS tile copy by a work-group of NW waves: each wave moves 64/NW rows of the tile.
+// Lane i of load instruction t moves one 16-byte chunk of tile row
+// (64/NW)*wave + 4*t + i/16 into LDS position (that row, chunk i%16); which global chunk it
 // fetches implements the swizzle.  A tile whose 64 keys are consecutive cache rows (the
 // common case) is addressed as a wave-uniform base plus a per-lane byte offset that never
 // changes, so the steady state spends no vector instructions on addresses.
@@ -199,8 +203,8 @@ struct Loader {     // scalars only, so that it is promoted to registers at once
   int seg_end0, seg_end1, seg_end2;  // visible key index -> cache row: vk + base of its segment
   int seg_base3, d2, d1, d0;         // base3, base2-base3, base1-base2, base0-base1
   int64_t row_bytes;                 // c_tok * 2
-  int row0;       // 16*wave + lane/16
-  int lds_row0;   // 16*wave
+  int row0;       // (64/NW)*wave + lane/16
+  int lds_row0;   // (64/NW)*wave
   int key_first;  // first visible key of this work-group's split
   int n_keys;
   uint32_t k_chunk_bytes[4], v_chunk_bytes[4];   // swizzled chunk offset inside a row (slow path)
@@ -212,7 +216,7 @@ __device__ __forceinline__ int seg_row(const Loader& L, int vk) {
          (vk < L.seg_end0 ? L.d0 : 0);
 }
 
-template <bool IS_V>
+template <bool IS_V, int NW>
 __device__ __forceinline__ void load_tile(const Loader& L, const LoaderOffsets& lo, int tile, uint8_t* dst_tile) {
   uint8_t* dst = dst_tile + L.lds_row0 * kRowBytes;
   const int k_first = L.key_first + tile * BN;   // wave-uniform
@@ -223,14 +227,14 @@ __device__ __forceinline__ void load_tile(const Loader& L, const LoaderOffsets& 
     // 64 consecutive cache rows: uniform base + constant per-lane offset
     const uint8_t* base = head + (int64_t)r_first * L.row_bytes;
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 16 / NW; ++t)
       __builtin_amdgcn_global_load_lds(GLB_PTR(base + (IS_V ? lo.v[t] : lo.k[t])),
                                        LDS_PTR(dst + t * 4 * kRowBytes), 16, 0, 0);
   } else {
     // tile straddles a segment boundary or the end of the keys: per-lane row lookup; rows
     // past the end re-read the last key (their scores are masked)
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < 16 / NW; ++t) {
       const int vk = min(k_first + L.row0 + 4 * t, L.n_keys - 1);
       const uint8_t* src = head + (int64_t)seg_row(L, vk) * L.row_bytes +
                            (IS_V ? L.v_chunk_bytes[t] : L.k_chunk_bytes[t]);
@@ -246,6 +250,7 @@ struct FragOffsets {
 
 // Iteration T: wait for K of tile T+1 and V of tile T, start the copies of K_{T+2} and V_{T+1}
 // into the two buffers nobody reads any more, then run the two 32-key sub-iterations.
+template <int NW>
 __device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, const LoaderOffsets& ch,
                                                const bf16x8_t (&qf)[8],
                                                const FragOffsets& fo, int T, int n_t, uint8_t* k_load,
@@ -254,16 +259,21 @@ __device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, c
   constexpr int kHalf = 32 * kRowBytes;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();   // K_{T+1}, V_T have landed; every wave is done with K_T and V_{T-1}
-  if (T + 2 < n_t) load_tile<false>(L, ch, T + 2, k_load);
-  load_tile<true>(L, ch, T + 1, v_load);
+  if (T + 2 < n_t) load_tile<false, NW>(L, ch, T + 2, k_load);
+  load_tile<true, NW>(L, ch, T + 1, v_load);
   sub_iteration<true, true, true>(st, qf, k_read, v_read, fo.k_off, fo.v_off, L.key_first + (2 * T + 2) * 32,
                                   L.n_keys, g, c, tau);
   sub_iteration<true, true, true>(st, qf, k_read + kHalf, v_read + kHalf, fo.k_off, fo.v_off,
                                   L.key_first + (2 * T + 3) * 32, L.n_keys, g, c, tau);
 }
 
-__global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
+// NW = waves per work-group (4 or 8), each owning 32 queries.  NW = 4: two work-groups per
+// CU.  NW = 8: one work-group per CU, so each K/V tile is copied into LDS once per CU
+// instead of twice (the copies cost matrix-pipe time), at a coarser query-tile granularity.
+template <int NW>
+__global__ __attribute__((amdgpu_flat_work_group_size(64 * NW, 64 * NW), amdgpu_waves_per_eu(2, 2)))
 void attention_kernel(AttnArgs a, SplitInfo sp) {
+  constexpr int BM = 32 * NW;   // queries per work-group
   // Four separate LDS objects (not one array): the compiler can then prove that the
   // fragment reads of one buffer do not alias the in-flight HBM->LDS copies into another,
   // and does not make the reads wait for the prefetch.
@@ -277,9 +287,16 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
   const int n = lane & 31;   // query column inside the wave's 32
   const int g = lane >> 5;   // which half of each 8-key group this lane holds
-  const int head = blockIdx.y;
-  const int split = blockIdx.z;
-  const int q0 = blockIdx.x * BM + wave * 32;
+  // Work-groups are dealt round-robin over the 8 XCDs (each with its own L2).  Give every XCD
+  // a contiguous run of the (head, split, query tile) list, so the work-groups that stream
+  // the same K/V rows at the same time share one L2.
+  const int unit = (int)(blockIdx.x % kXcds) * sp.units_per_xcd + (int)(blockIdx.x / kXcds);
+  if (unit >= sp.total_units) return;   // whole work-group leaves before any barrier
+  const int q_tile = unit % sp.q_tiles;
+  const int hs = unit / sp.q_tiles;
+  const int split = hs % sp.n_splits;
+  const int head = hs / sp.n_splits;
+  const int q0 = q_tile * BM + wave * 32;
   const int n_keys = (int)a.n_keys;
 
   const int n_tiles_total = (n_keys + BN - 1) / BN;
@@ -292,8 +309,8 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
     const int l_row = lane >> 4, l_chunk = lane & 15;
     L.row_bytes = a.c_tok * 2;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int row = 16 * wave + 4 * t + l_row;
+    for (int t = 0; t < 16 / NW; ++t) {
+      const int row = (64 / NW) * wave + 4 * t + l_row;
       L.k_chunk_bytes[t] = (l_chunk ^ (row & 15)) * 16;
       L.v_chunk_bytes[t] = ((((l_chunk >> 1) ^ (row & 3)) << 1) | (l_chunk & 1)) * 16;
       ch.k[t] = (uint32_t)(row * L.row_bytes) + L.k_chunk_bytes[t];
@@ -309,8 +326,8 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
     L.d2 = __builtin_amdgcn_readfirstlane(a.segs.base[2] - a.segs.base[3]);
     L.d1 = __builtin_amdgcn_readfirstlane(a.segs.base[1] - a.segs.base[2]);
     L.d0 = __builtin_amdgcn_readfirstlane(a.segs.base[0] - a.segs.base[1]);
-    L.row0 = 16 * wave + l_row;
-    L.lds_row0 = 16 * wave;
+    L.row0 = (64 / NW) * wave + l_row;
+    L.lds_row0 = (64 / NW) * wave;
     L.key_first = tile_begin * BN;
     L.n_keys = n_keys;
   }
@@ -361,9 +378,9 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   constexpr int kHalf = 32 * kRowBytes;
 
   // ---- prologue: S_0 and S_1 from tile 0, P_0
-  load_tile<false>(L, ch, 0, k_lds0);
-  load_tile<true>(L, ch, 0, v_lds0);
-  if (n_t > 1) load_tile<false>(L, ch, 1, k_lds1);
+  load_tile<false, NW>(L, ch, 0, k_lds0);
+  load_tile<true, NW>(L, ch, 0, v_lds0);
+  if (n_t > 1) load_tile<false, NW>(L, ch, 1, k_lds1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   {
@@ -380,11 +397,11 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   // ---- steady state: iteration T scores tile T+1 (K) and accumulates tile T (V)
   int T = 0;
   for (; T + 2 < n_t; T += 2) {
-    tile_iteration(st, L, ch, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);       // even T
-    tile_iteration(st, L, ch, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g, c, tau);   // odd T
+    tile_iteration<NW>(st, L, ch, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);       // even T
+    tile_iteration<NW>(st, L, ch, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g, c, tau);   // odd T
   }
   if (T + 1 < n_t) {
-    tile_iteration(st, L, ch, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);
+    tile_iteration<NW>(st, L, ch, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);
     ++T;
   }
   // ---- drain: T == n_t - 1; last tile's V, last block's softmax
@@ -469,58 +486,75 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a, SplitInfo sp) 
   if (a.lse && d4 == 0) a.lse[hq] = m * a.scale + logf(l);
 }
 
-constexpr int kSlots = 512;   // 256 CUs x 2 resident work-groups
+constexpr int kCus = 256;
 constexpr int kMaxSplits = 16;
 
-// Split the key range so that (query tiles x heads x splits) fills whole rounds of the
-// chip's work-group slots; every split costs a partial-result round trip, so a split must
-// pay for itself.
-int choose_splits(int n_q, int n_heads, int64_t n_keys) {
-  // CROPE_ATTN_SPLITS=<n> pins the number of key splits (tuning aid); unset or 0 = automatic
-  static const int forced = [] { const char* e = getenv("CROPE_ATTN_SPLITS"); return e ? atoi(e) : 0; }();
-  const int n_tiles_all = (int)((n_keys + BN - 1) / BN);
-  if (forced > 0) {
-    int s = forced < kMaxSplits ? forced : kMaxSplits;
-    while (s > 1 && (int64_t)(s - 1) * ((n_tiles_all + s - 1) / s) >= n_tiles_all) --s;   // no empty split
-    return s;
-  }
-  const int64_t units = (int64_t)((n_q + BM - 1) / BM) * n_heads;
+struct Plan {
+  int waves;    // waves per work-group: 4 (two work-groups per CU) or 8 (one)
+  int splits;   // key splits
+};
+
+// Pick the work-group shape and the number of key splits.  Cost = key tiles on the critical
+// path of the busiest CU slot, in units of one 4-wave work-group tile; an 8-wave work-group
+// shares its K/V copies between twice the queries and runs its tile ~12 % faster.  Every
+// split costs a partial-result round trip, so a split must pay for itself.
+Plan choose_plan(int n_q, int n_heads, int64_t n_keys) {
+  // CROPE_ATTN_SPLITS=<n> pins the number of key splits, CROPE_ATTN_WAVES=<4|8> the
+  // work-group shape (tuning aids); unset or 0 = automatic
+  static const int forced_s = [] { const char* e = getenv("CROPE_ATTN_SPLITS"); return e ? atoi(e) : 0; }();
+  static const int forced_w = [] { const char* e = getenv("CROPE_ATTN_WAVES"); return e ? atoi(e) : 0; }();
   const int n_tiles = (int)((n_keys + BN - 1) / BN);
-  int best = 1;
+  Plan best{4, 1};
   double best_cost = 1e30;
-  for (int s = 1; s <= kMaxSplits && s <= n_tiles; ++s) {
-    const int tiles_per = (n_tiles + s - 1) / s;
-    if ((int64_t)(s - 1) * tiles_per >= n_tiles) continue;   // would leave an empty split
-    const double rounds = (double)((units * s + kSlots - 1) / kSlots);
-    double cost = rounds * tiles_per;                         // key tiles on the critical path
-    if (s > 1) {
-      // fp32 partials are written and read back once: (128+2)*4 B per query, head and split,
-      // at ~4 TB/s, in units of one key tile of one work-group (~2 us); a split must also
-      // win by a clear margin
-      cost += 2.0 + (double)s * n_q * n_heads * 1040.0 / 8.4e6;
-      cost *= 1.05;
+  for (int nw = 4; nw <= 8; nw += 4) {
+    if ((forced_w == 4 || forced_w == 8) && nw != forced_w) continue;
+    const int bm = 32 * nw;
+    const int slots = kCus * (8 / nw);
+    const int64_t units = (int64_t)((n_q + bm - 1) / bm) * n_heads;
+    for (int s = 1; s <= kMaxSplits && s <= n_tiles; ++s) {
+      const int tiles_per = (n_tiles + s - 1) / s;
+      if ((int64_t)(s - 1) * tiles_per >= n_tiles) continue;   // would leave an empty split
+      if (forced_s > 0 && s != forced_s && !(s == 1 && forced_s > n_tiles)) continue;
+      const double rounds = (double)((units * s + slots - 1) / slots);
+      double cost = rounds * tiles_per * (nw == 8 ? 0.88 : 1.0);
+      if (s > 1) {
+        // fp32 partials are written and read back once: (128+2)*4 B per query, head and
+        // split, at ~4 TB/s, in units of one key tile (~2 us); a split must win clearly
+        cost += 2.0 + (double)s * n_q * n_heads * 1040.0 / 8.4e6;
+        cost *= 1.05;
+      }
+      if (cost < best_cost - 1e-9) { best_cost = cost; best = Plan{nw, s}; }
     }
-    if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
   }
   return best;
+}
+
+template <int NW>
+hipError_t launch_attention_t(const AttnArgs& a, SplitInfo sp, hipStream_t st) {
+  sp.q_tiles = (a.n_q + 32 * NW - 1) / (32 * NW);
+  const int64_t total_units = (int64_t)sp.q_tiles * a.n_heads * sp.n_splits;
+  if (total_units > (1 << 30)) return hipErrorInvalidValue;
+  sp.total_units = (int)total_units;
+  sp.units_per_xcd = (sp.total_units + kXcds - 1) / kXcds;
+  hipLaunchKernelGGL(attention_kernel<NW>, dim3(kXcds * sp.units_per_xcd), dim3(64 * NW), 0, st, a, sp);
+  return hipGetLastError();
 }
 
 }  // namespace
 
 size_t attention_workspace_bytes(int n_q, int n_heads, int64_t n_keys) {
-  const int s = choose_splits(n_q, n_heads, n_keys);
+  const int s = choose_plan(n_q, n_heads, n_keys).splits;
   if (s == 1) return 0;
   return (size_t)s * n_heads * n_q * (kHeadDim + 2) * sizeof(float);
 }
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
+  const Plan plan = choose_plan(a.n_q, a.n_heads, a.n_keys);
   SplitInfo sp;
-  sp.n_splits = choose_splits(a.n_q, a.n_heads, a.n_keys);
+  sp.n_splits = plan.splits;
   const int n_tiles = (int)((a.n_keys + BN - 1) / BN);
   sp.tiles_per_split = (n_tiles + sp.n_splits - 1) / sp.n_splits;
-  dim3 grid((a.n_q + BM - 1) / BM, a.n_heads, sp.n_splits);
-  hipLaunchKernelGGL(attention_kernel, grid, dim3(256), 0, st, a, sp);
-  hipError_t e = hipGetLastError();
+  hipError_t e = plan.waves == 8 ? launch_attention_t<8>(a, sp, st) : launch_attention_t<4>(a, sp, st);
   if (e != hipSuccess || sp.n_splits == 1) return e;
   const int64_t total = (int64_t)a.n_heads * a.n_q * (kHeadDim / 4);
   hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, sp);
