@@ -68,67 +68,41 @@ constexpr int kXcds = 8;
 // LDS layout of one K tile: row r (key), 16-byte chunk c (8 channels) at r*256 + ((c ^ (r&15))*16).
 // LDS layout of one V tile: row r, 32-byte pair slot p (16 channels) at r*256 + ((p ^ (r&3))*32).
 //
-// Software pipeline over 32-key blocks b (two per tile).  Sub-iteration b issues, as
-// independent instruction streams the hardware can overlap inside one wave,
+// Software pipeline over 32-key blocks b (two per tile).  Sub-iteration b holds three
+// independent instruction streams in ONE basic block, interleaved by the scheduler
+// directives at its end:
 //   MFMA:  S_{b+1} = K_{b+1} . Q^T          and   O^T += V_{b-1}^T . P_{b-1}^T
-//   VALU:  P_b = exp2(S_b * c - m_ref * c)  (row sums via bf16 dot products)
+//   VALU:  P_b = exp2(S_b * c - m_ref * c), row sums, and the block maximum of S_b
 // so K is needed one block ahead of V: tile T+1's K and tile T's V are live together, and
 // the four 16 KB LDS buffers hold K_{T+1}, K_{T+2} (arriving), V_T, V_{T+1} (arriving).
+// The probabilities are formed against the reference maximum as it stood BEFORE the block;
+// only afterwards is the block maximum compared with it, and in the rare case that it
+// exceeds the reference by more than 2^8 the block's probabilities are recomputed and the
+// running sums rescaled.  The score blocks alternate between two register sets.
 struct PipeState {
   f32x16_t o_acc[4];
-  f32x16_t s_cur;      // raw scores of the block whose softmax is due
-  f32x16_t s_init;     // accumulator seed of the next S block: 0, or -inf for keys past the end
+  f32x16_t s_a, s_b;   // raw scores: one block being exponentiated, the next being accumulated
   uint32_t p_prev[8];  // bf16 probabilities of the block whose P.V is due
   float m_ref, mc, l_run;
 };
 
-// key0_next: global index of the first key of the block whose scores this call computes.
-template <bool DO_S, bool DO_PV, bool DO_SOFTMAX>
-__device__ __forceinline__ void sub_iteration(PipeState& st, const bf16x8_t (&qf)[8],
+struct FragOffsets {
+  int k_off[8];
+  int v_off[4];
+};
+
+// key0_next: global index of the first key of the block scored by this call (S_{b+1}).
+template <bool DO_S, bool DO_PV, bool DO_SOFTMAX, bool MASK_S>
+__device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_in, f32x16_t& s_out,
+                                              const bf16x8_t (&qf)[8],
                                               const uint8_t* k_half,   // K rows of block b+1
                                               const uint8_t* v_half,   // V rows of block b-1
-                                              const int (&k_off)[8], const int (&v_off)[4],
-                                              int key0_next, int n_keys, int g, float c, float tau) {
-  // ---- rare events, decided wave-uniformly: the reference maximum must be raised, or the
-  // block about to be scored reaches beyond the last visible key
-  bool raise = false;
-  float mx = 0.f;
-  if (DO_SOFTMAX) {
-    mx = fmaxf(fmaxf(st.s_cur[0], st.s_cur[1]), st.s_cur[2]);
+                                              const FragOffsets& fo, int key0_next, int n_keys, int g,
+                                              float c, float tau) {
+  f32x16_t s_new;
 #pragma unroll
-    for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, st.s_cur[i]), st.s_cur[i + 1]);
-    mx = fmaxf(mx, st.s_cur[15]);
-    mx = max_across_halves(mx);
-    raise = mx > st.m_ref + tau;   // always true for the first block (m_ref = -inf)
-  }
-  const bool tail_next = DO_S && (key0_next + 32 > n_keys);
-  if (__builtin_amdgcn_ballot_w64(raise) != 0 || tail_next) {
-    if (DO_SOFTMAX) {
-      const float m_new = raise ? mx : st.m_ref;
-      const float alpha = __builtin_amdgcn_exp2f((st.m_ref - m_new) * c);   // 1 where unchanged
-      st.m_ref = m_new;
-      st.mc = m_new * c;
-      st.l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) st.o_acc[db][i] *= alpha;
-      if (DO_PV) {
-        // the pending probabilities were formed against the old reference
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-          st.p_prev[i] = pack_bf16x2(__uint_as_float(st.p_prev[i] << 16) * alpha,
-                                     __uint_as_float(st.p_prev[i] & 0xffff0000u) * alpha);
-      }
-    }
-    if (DO_S) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i)
-        st.s_init[i] = (key0_next + 8 * (i >> 2) + 4 * g + (i & 3) >= n_keys) ? -INFINITY : 0.f;
-    }
-  }
-  // ---- the overlapped part: one scheduling region whose instruction mix is pinned below
-  f32x16_t s_new = st.s_init;
+  for (int i = 0; i < 16; ++i)   // keys past the end are masked by seeding their scores with -inf
+    s_new[i] = (MASK_S && key0_next + 8 * (i >> 2) + 4 * g + (i & 3) >= n_keys) ? -INFINITY : 0.f;
   uint32_t p_new[8];
   const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
   bf16x8_t pb[2];
@@ -136,15 +110,15 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const bf16x8_t (&qf
     pb[0] = __builtin_bit_cast(bf16x8_t, make_uint4(st.p_prev[0], st.p_prev[1], st.p_prev[2], st.p_prev[3]));
     pb[1] = __builtin_bit_cast(bf16x8_t, make_uint4(st.p_prev[4], st.p_prev[5], st.p_prev[6], st.p_prev[7]));
   }
+  float l_new = st.l_run;
+  float mx = -INFINITY;
+  // Program order = the order in which the scheduler hands out fragment reads: V first (its
+  // MFMAs run first), then K (the S chain closes the block), then the softmax stream.
+  if (DO_PV) {
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    if (DO_S) {
-      const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(k_half + k_off[i]));
-      s_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[i], s_new, 0, 0, 0);
-    }
-    if (DO_PV) {
+    for (int i = 0; i < 8; ++i) {
       const int jj = i >> 2, db = i & 3;
-      const uint8_t* vp = v_half + v_off[db] + jj * 16 * kRowBytes;
+      const uint8_t* vp = v_half + fo.v_off[db] + jj * 16 * kRowBytes;
       const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(vp));
       const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
           (__attribute__((address_space(3))) s16x4_t*)(vp + 8 * kRowBytes));
@@ -152,62 +126,89 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const bf16x8_t (&qf
       const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
       st.o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[jj], st.o_acc[db], 0, 0, 0);
     }
-    if (DO_SOFTMAX) {
-      const float p0 = __builtin_amdgcn_exp2f(fmaf(st.s_cur[2 * i], c, -st.mc));
-      const float p1 = __builtin_amdgcn_exp2f(fmaf(st.s_cur[2 * i + 1], c, -st.mc));
-      const uint32_t u = pack_bf16x2(p0, p1);
-      p_new[i] = u;
-      // denominator from the rounded values the MFMA will see
-      st.l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, st.l_run, false);
-    }
   }
-  // Issue order: fragment reads run two steps ahead; every MFMA is followed by a few VALU /
-  // transcendental instructions of the (independent) softmax stream so that the matrix pipe
-  // and the vector ALU are busy at the same time inside this wave.
-  if (DO_S && DO_PV && DO_SOFTMAX) {
-    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);     // DS reads for steps 0 and 1
+  if (DO_S) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // VALU  (2 fma)
-      __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);   // TRANS (2 exp)
-      if (i < 6) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // DS reads for step i+2
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // VALU  (cvt, dot2, address)
+      const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(k_half + fo.k_off[i]));
+      s_new = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[i], s_new, 0, 0, 0);
     }
   }
   if (DO_SOFTMAX) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      // keep the softmax stream inside this scheduling region (it would otherwise be sunk
-      // to its first use in the next sub-iteration)
-      asm volatile("" : "+v"(p_new[i]));
-      st.p_prev[i] = p_new[i];
+      const float s0 = s_in[2 * i], s1 = s_in[2 * i + 1];
+      mx = fmaxf(fmaxf(mx, s0), s1);
+      const uint32_t u = pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(s0, c, -st.mc)),
+                                     __builtin_amdgcn_exp2f(fmaf(s1, c, -st.mc)));
+      p_new[i] = u;
+      // denominator from the rounded values the MFMA will see
+      l_new = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, l_new, false);
     }
-    asm volatile("" : "+v"(st.l_run));
   }
-  if (DO_S) st.s_cur = s_new;
+  // Issue order inside the block: a few fragment reads first, then every MFMA is followed by
+  // VALU / transcendental instructions of the softmax stream and the next fragment reads.
+  if (DO_S && DO_PV && DO_SOFTMAX) {
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);    // V fragments of the first four MFMAs
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // VALU
+      __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);   // TRANS
+      if (i < 8) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // DS reads, four MFMAs ahead
+    }
+  }
+  if (DO_SOFTMAX) {
+    // keep the softmax stream inside this scheduling region (it would otherwise be sunk to
+    // its first use in the next sub-iteration)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(p_new[i]));
+    asm volatile("" : "+v"(l_new), "+v"(mx));
+    // ---- rare: the block maximum outgrew the reference (always so for the first block)
+    mx = max_across_halves(mx);
+    const bool raise = mx > st.m_ref + tau;
+    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+      const float m_new = raise ? mx : st.m_ref;
+      const float alpha = __builtin_amdgcn_exp2f((st.m_ref - m_new) * c);   // 1 where unchanged, 0 at start
+      st.m_ref = m_new;
+      st.mc = m_new * c;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st.o_acc[db][i] *= alpha;
+      l_new = st.l_run * alpha;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t u = pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(s_in[2 * i], c, -st.mc)),
+                                       __builtin_amdgcn_exp2f(fmaf(s_in[2 * i + 1], c, -st.mc)));
+        p_new[i] = u;
+        l_new = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, l_new, false);
+      }
+    }
+    st.l_run = l_new;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) st.p_prev[i] = p_new[i];
+  }
+  if (DO_S) s_out = s_new;
 }
 
-// HBM -> LDS tile copy by a work-group of NW waves: each wave moves 64/NW rows of the tile.
-// Lane i of load instruction t moves one 16-byte chunk of tile row
-// (64/NW)*wave + 4*t + i/16 into LDS position (that row, chunk i%16); which global chunk it
-// fetches implements the swizzle.  A tile whose 64 keys are consecutive cache rows (the
-// common case) is addressed as a wave-uniform base plus a per-lane byte offset that never
-// changes, so the steady state spends no vector instructions on addresses.
-struct LoaderOffsets {
-  uint32_t k[4], v[4];   // byte offset of this lane's chunk from the tile's first row, per t
-};
+// HBM -> LDS tile copy by a work-group of NW waves.  Load instruction t of wave w moves tile
+// rows 4*NW*t + 4*w .. +3: lane i carries one 16-byte chunk of row 4*NW*t + 4*w + i/16 into LDS
+// position (that row, chunk i%16); which global chunk it fetches implements the swizzle,
+// which depends on the row only through 4*w + i/16, so one per-lane byte offset serves every
+// t.  A tile whose 64 keys are consecutive cache rows (the common case) is addressed as a
+// wave-uniform base plus that offset: no vector address arithmetic in the steady state.
 struct Loader {     // scalars only, so that it is promoted to registers at once
   const uint8_t *k_head, *v_head;    // cache base of this head (bytes)
   int seg_end0, seg_end1, seg_end2;  // visible key index -> cache row: vk + base of its segment
   int seg_base3, d2, d1, d0;         // base3, base2-base3, base1-base2, base0-base1
   int64_t row_bytes;                 // c_tok * 2
-  int row0;       // (64/NW)*wave + lane/16
-  int lds_row0;   // (64/NW)*wave
+  int row0;       // 4*wave + lane/16
+  int lds_row0;   // 4*wave
   int key_first;  // first visible key of this work-group's split
   int n_keys;
-  uint32_t k_chunk_bytes[4], v_chunk_bytes[4];   // swizzled chunk offset inside a row (slow path)
+  uint32_t k_chunk_bytes, v_chunk_bytes;   // swizzled chunk offset inside the lane's row
+  uint32_t k_lane_off, v_lane_off;         // row0 * row_bytes + chunk offset
 };
 
 __device__ __forceinline__ int seg_row(const Loader& L, int vk) {
@@ -217,7 +218,7 @@ __device__ __forceinline__ int seg_row(const Loader& L, int vk) {
 }
 
 template <bool IS_V, int NW>
-__device__ __forceinline__ void load_tile(const Loader& L, const LoaderOffsets& lo, int tile, uint8_t* dst_tile) {
+__device__ __forceinline__ void load_tile(const Loader& L, int tile, uint8_t* dst_tile) {
   uint8_t* dst = dst_tile + L.lds_row0 * kRowBytes;
   const int k_first = L.key_first + tile * BN;   // wave-uniform
   const int k_last = k_first + BN - 1;
@@ -226,50 +227,46 @@ __device__ __forceinline__ void load_tile(const Loader& L, const LoaderOffsets& 
   if (k_last < L.n_keys && seg_row(L, k_last) - r_first == BN - 1) {
     // 64 consecutive cache rows: uniform base + constant per-lane offset
     const uint8_t* base = head + (int64_t)r_first * L.row_bytes;
+    const uint32_t lane_off = IS_V ? L.v_lane_off : L.k_lane_off;
 #pragma unroll
     for (int t = 0; t < 16 / NW; ++t)
-      __builtin_amdgcn_global_load_lds(GLB_PTR(base + (IS_V ? lo.v[t] : lo.k[t])),
-                                       LDS_PTR(dst + t * 4 * kRowBytes), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(GLB_PTR(base + (int64_t)(4 * NW * t) * L.row_bytes + lane_off),
+                                       LDS_PTR(dst + t * 4 * NW * kRowBytes), 16, 0, 0);
   } else {
     // tile straddles a segment boundary or the end of the keys: per-lane row lookup; rows
     // past the end re-read the last key (their scores are masked)
 #pragma unroll
     for (int t = 0; t < 16 / NW; ++t) {
-      const int vk = min(k_first + L.row0 + 4 * t, L.n_keys - 1);
+      const int vk = min(k_first + L.row0 + 4 * NW * t, L.n_keys - 1);
       const uint8_t* src = head + (int64_t)seg_row(L, vk) * L.row_bytes +
-                           (IS_V ? L.v_chunk_bytes[t] : L.k_chunk_bytes[t]);
-      __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(dst + t * 4 * kRowBytes), 16, 0, 0);
+                           (IS_V ? L.v_chunk_bytes : L.k_chunk_bytes);
+      __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(dst + t * 4 * NW * kRowBytes), 16, 0, 0);
     }
   }
 }
 
-struct FragOffsets {
-  int k_off[8];
-  int v_off[4];
-};
-
 // Iteration T: wait for K of tile T+1 and V of tile T, start the copies of K_{T+2} and V_{T+1}
 // into the two buffers nobody reads any more, then run the two 32-key sub-iterations.
-template <int NW>
-__device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, const LoaderOffsets& ch,
-                                               const bf16x8_t (&qf)[8],
+// On entry st.s_b holds S of block 2T+1 and st.p_prev holds P of block 2T.
+template <int NW, bool MASK_S>
+__device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, const bf16x8_t (&qf)[8],
                                                const FragOffsets& fo, int T, int n_t, uint8_t* k_load,
                                                uint8_t* v_load, const uint8_t* k_read, const uint8_t* v_read,
                                                int g, float c, float tau) {
   constexpr int kHalf = 32 * kRowBytes;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();   // K_{T+1}, V_T have landed; every wave is done with K_T and V_{T-1}
-  if (T + 2 < n_t) load_tile<false, NW>(L, ch, T + 2, k_load);
-  load_tile<true, NW>(L, ch, T + 1, v_load);
-  sub_iteration<true, true, true>(st, qf, k_read, v_read, fo.k_off, fo.v_off, L.key_first + (2 * T + 2) * 32,
-                                  L.n_keys, g, c, tau);
-  sub_iteration<true, true, true>(st, qf, k_read + kHalf, v_read + kHalf, fo.k_off, fo.v_off,
-                                  L.key_first + (2 * T + 3) * 32, L.n_keys, g, c, tau);
+  if (T + 2 < n_t) load_tile<false, NW>(L, T + 2, k_load);
+  load_tile<true, NW>(L, T + 1, v_load);
+  sub_iteration<true, true, true, MASK_S>(st, st.s_b, st.s_a, qf, k_read, v_read, fo,
+                                          L.key_first + (2 * T + 2) * 32, L.n_keys, g, c, tau);
+  sub_iteration<true, true, true, MASK_S>(st, st.s_a, st.s_b, qf, k_read + kHalf, v_read + kHalf, fo,
+                                          L.key_first + (2 * T + 3) * 32, L.n_keys, g, c, tau);
 }
 
 // NW = waves per work-group (4 or 8), each owning 32 queries.  NW = 4: two work-groups per
 // CU.  NW = 8: one work-group per CU, so each K/V tile is copied into LDS once per CU
-// instead of twice (the copies cost matrix-pipe time), at a coarser query-tile granularity.
+// instead of twice, at a coarser query-tile granularity.
 template <int NW>
 __global__ __attribute__((amdgpu_flat_work_group_size(64 * NW, 64 * NW), amdgpu_waves_per_eu(2, 2)))
 void attention_kernel(AttnArgs a, SplitInfo sp) {
@@ -304,18 +301,14 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   const int n_t = min(n_tiles_total, tile_begin + sp.tiles_per_split) - tile_begin;   // >= 1
 
   Loader L;
-  LoaderOffsets ch;
   {
     const int l_row = lane >> 4, l_chunk = lane & 15;
+    const int row = 4 * wave + l_row;   // the lane's row inside every 4*NW-row group
     L.row_bytes = a.c_tok * 2;
-#pragma unroll
-    for (int t = 0; t < 16 / NW; ++t) {
-      const int row = (64 / NW) * wave + 4 * t + l_row;
-      L.k_chunk_bytes[t] = (l_chunk ^ (row & 15)) * 16;
-      L.v_chunk_bytes[t] = ((((l_chunk >> 1) ^ (row & 3)) << 1) | (l_chunk & 1)) * 16;
-      ch.k[t] = (uint32_t)(row * L.row_bytes) + L.k_chunk_bytes[t];
-      ch.v[t] = (uint32_t)(row * L.row_bytes) + L.v_chunk_bytes[t];
-    }
+    L.k_chunk_bytes = (l_chunk ^ (row & 15)) * 16;
+    L.v_chunk_bytes = ((((l_chunk >> 1) ^ (row & 3)) << 1) | (l_chunk & 1)) * 16;
+    L.k_lane_off = (uint32_t)(row * L.row_bytes) + L.k_chunk_bytes;
+    L.v_lane_off = (uint32_t)(row * L.row_bytes) + L.v_chunk_bytes;
     L.k_head = reinterpret_cast<const uint8_t*>(a.k_cache + (int64_t)head * a.c_head);
     L.v_head = reinterpret_cast<const uint8_t*>(a.v_cache + (int64_t)head * a.c_head);
     // through readfirstlane: plain scalar values, not addresses the compiler may select between
@@ -326,8 +319,8 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
     L.d2 = __builtin_amdgcn_readfirstlane(a.segs.base[2] - a.segs.base[3]);
     L.d1 = __builtin_amdgcn_readfirstlane(a.segs.base[1] - a.segs.base[2]);
     L.d0 = __builtin_amdgcn_readfirstlane(a.segs.base[0] - a.segs.base[1]);
-    L.row0 = (64 / NW) * wave + l_row;
-    L.lds_row0 = (64 / NW) * wave;
+    L.row0 = row;
+    L.lds_row0 = 4 * wave;
     L.key_first = tile_begin * BN;
     L.n_keys = n_keys;
   }
@@ -346,10 +339,8 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   // ---- fragment read offsets (bytes inside a 32-key half tile)
   // K: row n, logical chunk 2*ks + g  ->  (2*ks) ^ (g ^ (n&15)) after the swizzle
   FragOffsets fo;
-  int (&k_off)[8] = fo.k_off;
-  int (&v_off)[4] = fo.v_off;
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) k_off[ks] = n * kRowBytes + (((2 * ks + g) ^ (n & 15)) << 4);
+  for (int ks = 0; ks < 8; ++ks) fo.k_off[ks] = n * kRowBytes + (((2 * ks + g) ^ (n & 15)) << 4);
   // V (transposing read): 16-lane group G = lane/16 covers channel half mh = G&1 of key half g;
   // lane i of the group points at row 4g + i/4 (+ step offset), channels 16*(db + 4*mh) + 4*(i%4)
   {
@@ -357,7 +348,7 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
     const int kk = i16 >> 2, cc = i16 & 3;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
-      v_off[db] = (4 * g + kk) * kRowBytes + (((db ^ kk) + 4 * mh) << 5) + cc * 8;
+      fo.v_off[db] = (4 * g + kk) * kRowBytes + (((db ^ kk) + 4 * mh) << 5) + cc * 8;
   }
 
   PipeState st;
@@ -365,8 +356,6 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) st.o_acc[db][i] = 0.f;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) st.s_init[i] = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i) st.p_prev[i] = 0u;
   const float c = a.scale * kLog2e;   // exp(x*scale) = exp2(x*c)
@@ -377,31 +366,31 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   const int key_base = tile_begin * BN;
   constexpr int kHalf = 32 * kRowBytes;
 
-  // ---- prologue: S_0 and S_1 from tile 0, P_0
-  load_tile<false, NW>(L, ch, 0, k_lds0);
-  load_tile<true, NW>(L, ch, 0, v_lds0);
-  if (n_t > 1) load_tile<false, NW>(L, ch, 1, k_lds1);
+  // ---- prologue: S_0 -> s_a and S_1 -> s_b from tile 0, then P_0
+  load_tile<false, NW>(L, 0, k_lds0);
+  load_tile<true, NW>(L, 0, v_lds0);
+  if (n_t > 1) load_tile<false, NW>(L, 1, k_lds1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  {
-    st.s_cur = st.s_init;   // zeros; replaced by S_0 below
-    sub_iteration<true, false, false>(st, qf, k_lds0, nullptr, k_off, v_off, key_base, n_keys, g, c, tau);
-    const f32x16_t s0 = st.s_cur;
-    sub_iteration<true, false, false>(st, qf, k_lds0 + kHalf, nullptr, k_off, v_off, key_base + 32, n_keys, g, c, tau);
-    const f32x16_t s1 = st.s_cur;
-    st.s_cur = s0;
-    sub_iteration<false, false, true>(st, qf, nullptr, nullptr, k_off, v_off, 0, n_keys, g, c, tau);   // P_0
-    st.s_cur = s1;
-  }
+  sub_iteration<true, false, false, true>(st, st.s_a, st.s_a, qf, k_lds0, nullptr, fo, key_base, n_keys, g, c, tau);
+  sub_iteration<true, false, false, true>(st, st.s_b, st.s_b, qf, k_lds0 + kHalf, nullptr, fo, key_base + 32, n_keys,
+                                          g, c, tau);
+  sub_iteration<false, false, true, false>(st, st.s_a, st.s_a, qf, nullptr, nullptr, fo, 0, n_keys, g, c, tau);
 
   // ---- steady state: iteration T scores tile T+1 (K) and accumulates tile T (V)
   int T = 0;
-  for (; T + 2 < n_t; T += 2) {
-    tile_iteration<NW>(st, L, ch, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);       // even T
-    tile_iteration<NW>(st, L, ch, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g, c, tau);   // odd T
+  for (; T + 3 < n_t; T += 2) {
+    tile_iteration<NW, false>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);       // even T
+    tile_iteration<NW, false>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g, c, tau);   // odd T
   }
+  if (T + 2 < n_t) {
+    tile_iteration<NW, false>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);
+    ++T;
+  }
+  // ---- T == n_t - 2 scores the last tile, which may reach beyond the visible keys
   if (T + 1 < n_t) {
-    tile_iteration<NW>(st, L, ch, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);
+    if (T & 1) tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g, c, tau);
+    else tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);
     ++T;
   }
   // ---- drain: T == n_t - 1; last tile's V, last block's softmax
@@ -409,8 +398,8 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const uint8_t* vb = (T & 1) ? v_lds1 : v_lds0;
-    sub_iteration<false, true, true>(st, qf, nullptr, vb, k_off, v_off, 0, n_keys, g, c, tau);
-    sub_iteration<false, true, false>(st, qf, nullptr, vb + kHalf, k_off, v_off, 0, n_keys, g, c, tau);
+    sub_iteration<false, true, true, false>(st, st.s_b, st.s_b, qf, nullptr, vb, fo, 0, n_keys, g, c, tau);
+    sub_iteration<false, true, false, false>(st, st.s_a, st.s_a, qf, nullptr, vb + kHalf, fo, 0, n_keys, g, c, tau);
   }
   f32x16_t* o_acc = st.o_acc;
   const float m_ref = st.m_ref, l_run = st.l_run;
