@@ -25,16 +25,16 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # by what the same counter reads for a 1 GiB copy (x2.000 and x1.000); the summary with the
 # commands is profiles/chunk_attention_and_rope_C4_pmc.md.  Other workloads report null.
 MEASURED_TRAFFIC_BYTES = {
-    "C4": {"chunk_attention": (837675.7 * 2.000 + 14040.3 * 1.000) * 1024,
-           "crope_qk_norm_rotate_append": (21216.8 * 2.000 + 42120.0 * 1.000) * 1024},
+    "C4": {"chunk_attention": (162805.9 * 2.000 + 16776.1 * 1.000) * 1024,
+           "crope_qk_norm_rotate_append": (21203.3 * 2.000 + 42120.0 * 1.000) * 1024},
 }
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=1024,
@@ -117,14 +117,34 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
-    # per-kernel durations with events on the launch stream (separate pass, same work)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    for i in range(args.steps):
-        step(i, evs[i])
+    # per-kernel average launch duration with events on the launch stream: K back-to-back
+    # launches of one kernel between two events (an event pair around a single 20 us kernel
+    # would add its own few microseconds), same work as the timed steps
+    def timed(fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(args.steps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    def rope_only(i):
+        q, k, v = sets[i % len(sets)]
+        P.crope_qk_norm_rotate_append(desc, tab, q, k, v, gq, gk, cfg.eps, group, n, H, cfg.grid_h,
+                                      cfg.grid_w, s, off, q_rot, k_cache, v_cache, cap, dst)
+
+    def attn_only(i):
+        P.chunk_attention(q_rot, cfg.n_q, H, k_cache, v_cache, cap, segs, Hn.SCALE, out, lse, ws,
+                          ws_bytes)
+
+    rope_runs = [timed(rope_only) for _ in range(3)]
+    attn_runs = [timed(attn_only) for _ in range(3)]
+    rope_ms, attn_ms = float(np.mean(rope_runs)), float(np.mean(attn_runs))
+    t_rope, t_attn = np.array(rope_runs), np.array(attn_runs)
+    step(0)   # leave out/lse holding the result of a whole step for the parity sample
     torch.cuda.synchronize()
-    t_rope = np.array([e[0].elapsed_time(e[1]) for e in evs])     # ms
-    t_attn = np.array([e[1].elapsed_time(e[2]) for e in evs])
-    rope_ms, attn_ms = float(t_rope.mean()), float(t_attn.mean())
 
     flops = cfg.attention_flops
     rope_bytes = cfg.rope_bytes

@@ -1,7 +1,8 @@
 // Rotary table build and the fused qk-RMSNorm + causal 3D RoPE + KV-cache update kernel.
 //
 // The fused kernel is bandwidth-bound: per token it reads q, k, v (3 * H*128 bf16) and
-// writes rotated q, rotated k, v (another 3 * H*128 bf16).  One 64-lane wave owns one token;
+// writes rotated q, rotated k, v (another 3 * H*128 bf16).  One 64-lane wave owns one token
+// of one of the three tensors;
 // every lane moves 16-byte pieces (8 channels of one head), so a wave's requests cover
 // whole contiguous 1 KB spans.  Statistics are fp32, reduced across the wave with
 // cross-lane shuffles; nothing is staged through LDS.
@@ -12,6 +13,7 @@ namespace {
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   f32x2_t f = {lo, hi};
@@ -63,27 +65,41 @@ __device__ __forceinline__ float group16_sum(float x) {
 // ITERS = ceil(n_heads / 4): lane l owns 16-byte chunk c = l + 64*it of the token's H*16
 // chunks; chunk c is head c/16, channels 8*(c%16)..+7, and c%16 == l%16 for every it, so a
 // lane's four rotation angles are the same for all of its chunks.
+//
+// blockIdx.y selects the tensor a work-group handles (0: q, 1: k, 2: v).  Splitting the
+// three tensors over different waves triples the number of independent load/store streams in
+// flight and lets one wave's stores overlap another's loads; v is a plain copy.
 template <int ITERS>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void rope_kernel(RopeArgs a) {
   const int lane = threadIdx.x & 63;
   const int tok = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   if (tok >= a.n_tokens) return;
   const int n_chunks = a.n_heads * 16;
-
-  // issue all loads first: q, k, v chunks of this lane
-  uint4 rq[ITERS], rk[ITERS], rv[ITERS];
+  const int role = blockIdx.y;
+  const uint16_t* src = role == 0 ? a.q : role == 1 ? a.k : a.v;
   const int64_t in_base = (int64_t)tok * a.in_tok;
+  const int64_t c_base = (a.dst_token + tok) * a.c_tok;
+
+  // issue all loads first
+  uint4 rx[ITERS];
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
     const int c = lane + 64 * it;
-    if (c < n_chunks) {
-      const int64_t off = in_base + (int64_t)(c >> 4) * a.in_head + (c & 15) * 8;
-      rq[it] = *reinterpret_cast<const uint4*>(a.q + off);
-      rk[it] = *reinterpret_cast<const uint4*>(a.k + off);
-      rv[it] = *reinterpret_cast<const uint4*>(a.v + off);
-    } else {
-      rq[it] = make_uint4(0, 0, 0, 0); rk[it] = rq[it]; rv[it] = rq[it];
+    if (c < n_chunks)
+      rx[it] = __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(
+                                             src + in_base + (int64_t)(c >> 4) * a.in_head + (c & 15) * 8)));
+    else
+      rx[it] = make_uint4(0, 0, 0, 0);
+  }
+
+  if (role == 2) {   // v goes to the cache untouched
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int c = lane + 64 * it;
+      if (c < n_chunks)
+        *reinterpret_cast<uint4*>(a.v_cache + c_base + (int64_t)(c >> 4) * a.c_head + (c & 15) * 8) = rx[it];
     }
+    return;
   }
 
   // global position of this token (index decode with the global time index)
@@ -100,98 +116,72 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rope_kernel(RopeArgs a) {
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const int j = 4 * (lane & 15) + p;
-    const float* src;
-    if (j < a.tl.pairs_t) src = a.table + a.tl.off_t + ((int64_t)pt * a.tl.pairs_t + j) * 2;
+    const float* tsrc;
+    if (j < a.tl.pairs_t) tsrc = a.table + a.tl.off_t + ((int64_t)pt * a.tl.pairs_t + j) * 2;
     else if (j < a.tl.pairs_t + a.tl.pairs_h)
-      src = a.table + a.tl.off_h + ((int64_t)ph * a.tl.pairs_h + (j - a.tl.pairs_t)) * 2;
+      tsrc = a.table + a.tl.off_h + ((int64_t)ph * a.tl.pairs_h + (j - a.tl.pairs_t)) * 2;
     else
-      src = a.table + a.tl.off_w + ((int64_t)pw * a.tl.pairs_w + (j - a.tl.pairs_t - a.tl.pairs_h)) * 2;
-    const float2 t = *reinterpret_cast<const float2*>(src);
+      tsrc = a.table + a.tl.off_w + ((int64_t)pw * a.tl.pairs_w + (j - a.tl.pairs_t - a.tl.pairs_h)) * 2;
+    const float2 t = *reinterpret_cast<const float2*>(tsrc);
     cs[p] = t.x; sn[p] = t.y;
   }
 
-  // v goes to the cache untouched
-  const int64_t c_base = (a.dst_token + tok) * a.c_tok;
-#pragma unroll
-  for (int it = 0; it < ITERS; ++it) {
-    const int c = lane + 64 * it;
-    if (c < n_chunks)
-      *reinterpret_cast<uint4*>(a.v_cache + c_base + (int64_t)(c >> 4) * a.c_head + (c & 15) * 8) = rv[it];
-  }
-
   // sums of squares
-  float ssq[ITERS], ssk[ITERS];
+  float ss[ITERS];
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
-    const uint32_t* uq = reinterpret_cast<const uint32_t*>(&rq[it]);
-    const uint32_t* uk = reinterpret_cast<const uint32_t*>(&rk[it]);
-    float sq = 0.f, sk = 0.f;
+    const uint32_t* u = reinterpret_cast<const uint32_t*>(&rx[it]);
+    float sq = 0.f;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      float x0 = bf16_lo(uq[e]), x1 = bf16_hi(uq[e]);
-      float y0 = bf16_lo(uk[e]), y1 = bf16_hi(uk[e]);
+      const float x0 = bf16_lo(u[e]), x1 = bf16_hi(u[e]);
       sq = fmaf(x0, x0, sq); sq = fmaf(x1, x1, sq);
-      sk = fmaf(y0, y0, sk); sk = fmaf(y1, y1, sk);
     }
-    ssq[it] = sq; ssk[it] = sk;
+    ss[it] = sq;
   }
-  float rq_scale[ITERS], rk_scale[ITERS];
+  float r_scale[ITERS];
   if (a.per_head_norm) {
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-      const float tq = group16_sum(ssq[it]);
-      const float tk = group16_sum(ssk[it]);
-      rq_scale[it] = 1.0f / sqrtf(tq * (1.0f / kHeadDim) + a.eps);
-      rk_scale[it] = 1.0f / sqrtf(tk * (1.0f / kHeadDim) + a.eps);
-    }
+    for (int it = 0; it < ITERS; ++it)
+      r_scale[it] = 1.0f / sqrtf(group16_sum(ss[it]) * (1.0f / kHeadDim) + a.eps);
   } else {
-    float tq = 0.f, tk = 0.f;
+    float t = 0.f;
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) { tq += ssq[it]; tk += ssk[it]; }
-    tq = wave_sum(tq); tk = wave_sum(tk);
-    const float inv_n = 1.0f / (float)(a.n_heads * kHeadDim);
-    const float sq = 1.0f / sqrtf(tq * inv_n + a.eps);
-    const float sk = 1.0f / sqrtf(tk * inv_n + a.eps);
+    for (int it = 0; it < ITERS; ++it) t += ss[it];
+    t = wave_sum(t);
+    const float sc = 1.0f / sqrtf(t * (1.0f / (float)(a.n_heads * kHeadDim)) + a.eps);
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) { rq_scale[it] = sq; rk_scale[it] = sk; }
+    for (int it = 0; it < ITERS; ++it) r_scale[it] = sc;
   }
 
   // normalise, apply gain, rotate, round once to bf16, store
-  const int64_t qo_base = (int64_t)tok * a.qo_tok;
+  const float* gain = role == 0 ? a.gain_q : a.gain_k;
+  uint16_t* dst = role == 0 ? a.q_out + (int64_t)tok * a.qo_tok : a.k_cache + c_base;
+  const int64_t dst_head = role == 0 ? a.qo_head : a.c_head;
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
     const int c = lane + 64 * it;
     if (c >= n_chunks) continue;
     const int head = c >> 4, d0 = (c & 15) * 8;
-    const float4 gq0 = *reinterpret_cast<const float4*>(a.gain_q + head * kHeadDim + d0);
-    const float4 gq1 = *reinterpret_cast<const float4*>(a.gain_q + head * kHeadDim + d0 + 4);
-    const float4 gk0 = *reinterpret_cast<const float4*>(a.gain_k + head * kHeadDim + d0);
-    const float4 gk1 = *reinterpret_cast<const float4*>(a.gain_k + head * kHeadDim + d0 + 4);
-    const float gq[8] = {gq0.x, gq0.y, gq0.z, gq0.w, gq1.x, gq1.y, gq1.z, gq1.w};
-    const float gk[8] = {gk0.x, gk0.y, gk0.z, gk0.w, gk1.x, gk1.y, gk1.z, gk1.w};
-    const uint32_t* uq = reinterpret_cast<const uint32_t*>(&rq[it]);
-    const uint32_t* uk = reinterpret_cast<const uint32_t*>(&rk[it]);
-    uint32_t oq[4], ok[4];
+    const float4 g0 = *reinterpret_cast<const float4*>(gain + head * kHeadDim + d0);
+    const float4 g1 = *reinterpret_cast<const float4*>(gain + head * kHeadDim + d0 + 4);
+    const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+    const uint32_t* u = reinterpret_cast<const uint32_t*>(&rx[it]);
+    uint32_t o[4];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      const float qa = bf16_lo(uq[p]) * rq_scale[it] * gq[2 * p];
-      const float qb = bf16_hi(uq[p]) * rq_scale[it] * gq[2 * p + 1];
-      const float ka = bf16_lo(uk[p]) * rk_scale[it] * gk[2 * p];
-      const float kb = bf16_hi(uk[p]) * rk_scale[it] * gk[2 * p + 1];
-      oq[p] = pack_bf16x2(qa * cs[p] - qb * sn[p], qa * sn[p] + qb * cs[p]);
-      ok[p] = pack_bf16x2(ka * cs[p] - kb * sn[p], ka * sn[p] + kb * cs[p]);
+      const float xa = bf16_lo(u[p]) * r_scale[it] * gg[2 * p];
+      const float xb = bf16_hi(u[p]) * r_scale[it] * gg[2 * p + 1];
+      o[p] = pack_bf16x2(xa * cs[p] - xb * sn[p], xa * sn[p] + xb * cs[p]);
     }
-    *reinterpret_cast<uint4*>(a.q_out + qo_base + (int64_t)head * a.qo_head + d0) =
-        make_uint4(oq[0], oq[1], oq[2], oq[3]);
-    *reinterpret_cast<uint4*>(a.k_cache + c_base + (int64_t)head * a.c_head + d0) =
-        make_uint4(ok[0], ok[1], ok[2], ok[3]);
+    *reinterpret_cast<uint4*>(dst + (int64_t)head * dst_head + d0) = make_uint4(o[0], o[1], o[2], o[3]);
   }
 }
 
 template <int ITERS>
 hipError_t launch_rope_t(const RopeArgs& a, hipStream_t st) {
   const int blocks = (a.n_tokens + kWavesPerBlock - 1) / kWavesPerBlock;
-  hipLaunchKernelGGL(rope_kernel<ITERS>, dim3(blocks), dim3(64 * kWavesPerBlock), 0, st, a);
+  hipLaunchKernelGGL(rope_kernel<ITERS>, dim3(blocks, 3), dim3(64 * kWavesPerBlock), 0, st, a);
   return hipGetLastError();
 }
 
