@@ -51,7 +51,7 @@ constexpr int BN = 64;                  // keys per tile
 constexpr int kRowBytes = kHeadDim * 2; // 256 B per key row in LDS (swizzled, unpadded)
 constexpr int kTileBytes = BN * kRowBytes;   // 16 KB
 constexpr float kLog2e = 1.44269504088896340736f;
-// A query's reference maximum is only raised when a block's maximum exceeds it by more than
+// A query's reference maximum is only raised when a tile's maximum exceeds it by more than
 // this many powers of two; until then probabilities may exceed 1 (at most 2^8), which fp32
 // accumulators and bf16's exponent range absorb, and the O rescale is skipped.
 constexpr float kRescaleLog2 = 8.0f;
@@ -72,7 +72,7 @@ constexpr int kXcds = 8;
 // independent instruction streams in ONE basic block, interleaved by the scheduler
 // directives at its end:
 //   MFMA:  S_{b+1} = K_{b+1} . Q^T          and   O^T += V_{b-1}^T . P_{b-1}^T
-//   VALU:  P_b = exp2(S_b) (S_b is already the base-2 exponent), row sums, block maximum of S_b
+//   VALU:  P_b = exp2(S_b * c - m_ref * c), row sums, and the block maximum of S_b
 // so K is needed one block ahead of V: tile T+1's K and tile T's V are live together, and
 // the four 16 KB LDS buffers hold K_{T+1}, K_{T+2} (arriving), V_T, V_{T+1} (arriving).
 // The probabilities are formed against the reference maximum as it stood BEFORE the block;
@@ -81,11 +81,9 @@ constexpr int kXcds = 8;
 // running sums rescaled.  The score blocks alternate between two register sets.
 struct PipeState {
   f32x16_t o_acc[4];
-  f32x16_t s_a, s_b;   // exponents: one block being exponentiated, the next being accumulated
-  f32x16_t seed;       // -m (log2 units) in every element: the accumulator seed of an S block
+  f32x16_t s_a, s_b;   // raw scores: one block being exponentiated, the next being accumulated
   uint32_t p_prev[8];  // bf16 probabilities of the block whose P.V is due
-  float m_log2;        // reference maximum of query n, in log2 units (scale*log2(e) folded in)
-  float l_run;         // this lane's share of the denominator
+  float m_ref, mc, l_run;
 };
 
 struct FragOffsets {
@@ -93,22 +91,18 @@ struct FragOffsets {
   int v_off[4];
 };
 
-// The queries are pre-multiplied by scale*log2(e) and every S accumulator is seeded with -m,
-// so an MFMA chain delivers the exponent e = log2(p) directly and the softmax stream is one
-// v_exp_f32 per score plus max / convert / sum.  key0_next: global index of the first key of
-// the block scored by this call (S_{b+1}).  pending: a score block already computed against
-// the current reference that must follow a change of it (prologue only).
-template <bool DO_S, bool DO_PV, bool DO_SOFTMAX, bool MASK_S, bool FIRST>
+// key0_next: global index of the first key of the block scored by this call (S_{b+1}).
+template <bool DO_S, bool DO_PV, bool DO_SOFTMAX, bool MASK_S>
 __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_in, f32x16_t& s_out,
                                               const bf16x8_t (&qf)[8],
                                               const uint8_t* k_half,   // K rows of block b+1
                                               const uint8_t* v_half,   // V rows of block b-1
                                               const FragOffsets& fo, int key0_next, int n_keys, int g,
-                                              f32x16_t* pending) {
+                                              float c, float tau) {
   f32x16_t s_new;
 #pragma unroll
   for (int i = 0; i < 16; ++i)   // keys past the end are masked by seeding their scores with -inf
-    s_new[i] = (MASK_S && key0_next + 8 * (i >> 2) + 4 * g + (i & 3) >= n_keys) ? -INFINITY : st.seed[i];
+    s_new[i] = (MASK_S && key0_next + 8 * (i >> 2) + 4 * g + (i & 3) >= n_keys) ? -INFINITY : 0.f;
   uint32_t p_new[8];
   const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
   bf16x8_t pb[2];
@@ -143,9 +137,10 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_i
   if (DO_SOFTMAX) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const float e0 = s_in[2 * i], e1 = s_in[2 * i + 1];
-      mx = fmaxf(fmaxf(mx, e0), e1);
-      const uint32_t u = pack_bf16x2(__builtin_amdgcn_exp2f(e0), __builtin_amdgcn_exp2f(e1));
+      const float s0 = s_in[2 * i], s1 = s_in[2 * i + 1];
+      mx = fmaxf(fmaxf(mx, s0), s1);
+      const uint32_t u = pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(s0, c, -st.mc)),
+                                     __builtin_amdgcn_exp2f(fmaf(s1, c, -st.mc)));
       p_new[i] = u;
       // denominator from the rounded values the MFMA will see
       l_new = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, l_new, false);
@@ -158,7 +153,7 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_i
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // VALU
+      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // VALU
       __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);   // TRANS
       if (i < 8) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // DS reads, four MFMAs ahead
     }
@@ -169,16 +164,14 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_i
 #pragma unroll
     for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(p_new[i]));
     asm volatile("" : "+v"(l_new), "+v"(mx));
-    // ---- rare: the block maximum outgrew the reference by more than 2^8 (the first block
-    // always re-centres, in either direction)
+    // ---- rare: the block maximum outgrew the reference (always so for the first block)
     mx = max_across_halves(mx);
-    const bool raise = FIRST || mx > kRescaleLog2;
+    const bool raise = mx > st.m_ref + tau;
     if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-      const float delta = raise ? mx : 0.f;
-      const float alpha = __builtin_amdgcn_exp2f(-delta);
-      st.m_log2 += delta;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) st.seed[i] = -st.m_log2;
+      const float m_new = raise ? mx : st.m_ref;
+      const float alpha = __builtin_amdgcn_exp2f((st.m_ref - m_new) * c);   // 1 where unchanged, 0 at start
+      st.m_ref = m_new;
+      st.mc = m_new * c;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -186,19 +179,10 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_i
       l_new = st.l_run * alpha;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const uint32_t u = pack_bf16x2(__builtin_amdgcn_exp2f(s_in[2 * i] - delta),
-                                       __builtin_amdgcn_exp2f(s_in[2 * i + 1] - delta));
+        const uint32_t u = pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(s_in[2 * i], c, -st.mc)),
+                                       __builtin_amdgcn_exp2f(fmaf(s_in[2 * i + 1], c, -st.mc)));
         p_new[i] = u;
         l_new = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, l_new, false);
-      }
-      // score blocks already seeded with the old reference follow it
-      if (DO_S) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s_new[i] -= delta;
-      }
-      if (pending) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) (*pending)[i] -= delta;
       }
     }
     st.l_run = l_new;
@@ -268,16 +252,16 @@ template <int NW, bool MASK_S>
 __device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, const bf16x8_t (&qf)[8],
                                                const FragOffsets& fo, int T, int n_t, uint8_t* k_load,
                                                uint8_t* v_load, const uint8_t* k_read, const uint8_t* v_read,
-                                               int g) {
+                                               int g, float c, float tau) {
   constexpr int kHalf = 32 * kRowBytes;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();   // K_{T+1}, V_T have landed; every wave is done with K_T and V_{T-1}
   if (T + 2 < n_t) load_tile<false, NW>(L, T + 2, k_load);
   load_tile<true, NW>(L, T + 1, v_load);
-  sub_iteration<true, true, true, MASK_S, false>(st, st.s_b, st.s_a, qf, k_read, v_read, fo,
-                                                 L.key_first + (2 * T + 2) * 32, L.n_keys, g, nullptr);
-  sub_iteration<true, true, true, MASK_S, false>(st, st.s_a, st.s_b, qf, k_read + kHalf, v_read + kHalf, fo,
-                                                 L.key_first + (2 * T + 3) * 32, L.n_keys, g, nullptr);
+  sub_iteration<true, true, true, MASK_S>(st, st.s_b, st.s_a, qf, k_read, v_read, fo,
+                                          L.key_first + (2 * T + 2) * 32, L.n_keys, g, c, tau);
+  sub_iteration<true, true, true, MASK_S>(st, st.s_a, st.s_b, qf, k_read + kHalf, v_read + kHalf, fo,
+                                          L.key_first + (2 * T + 3) * 32, L.n_keys, g, c, tau);
 }
 
 // NW = waves per work-group (4 or 8), each owning 32 queries.  NW = 4: two work-groups per
@@ -341,24 +325,15 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
     L.n_keys = n_keys;
   }
 
-  // ---- Q^T fragments (B operand): lane holds query n, channels 16*ks + 8g .. +7, multiplied
-  // by scale*log2(e) (one more bf16 rounding of q) so that q.k is the base-2 exponent
-  const float c = a.scale * kLog2e;   // exp(x*scale) = exp2(x*c)
+  // ---- Q^T fragments (B operand): lane holds query n, channels 16*ks + 8g .. +7
   bf16x8_t qf[8];
   {
     int qrow = q0 + n;
     if (qrow >= a.n_q) qrow = a.n_q - 1;
     const uint16_t* qp = a.q + (int64_t)qrow * a.q_tok + (int64_t)head * a.q_head + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(qp + 16 * ks);
-      const uint32_t r[4] = {raw.x, raw.y, raw.z, raw.w};
-      uint32_t o[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        o[e] = pack_bf16x2(__uint_as_float(r[e] << 16) * c, __uint_as_float(r[e] & 0xffff0000u) * c);
-      qf[ks] = __builtin_bit_cast(bf16x8_t, make_uint4(o[0], o[1], o[2], o[3]));
-    }
+    for (int ks = 0; ks < 8; ++ks)
+      qf[ks] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(qp + 16 * ks));
   }
 
   // ---- fragment read offsets (bytes inside a 32-key half tile)
@@ -382,11 +357,12 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) st.o_acc[db][i] = 0.f;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) st.seed[i] = 0.f;
-#pragma unroll
   for (int i = 0; i < 8; ++i) st.p_prev[i] = 0u;
-  st.m_log2 = 0.f;   // provisional reference; the first block re-centres on its own maximum
-  st.l_run = 0.f;
+  const float c = a.scale * kLog2e;   // exp(x*scale) = exp2(x*c)
+  const float tau = kRescaleLog2 / c; // in raw score units
+  st.m_ref = -INFINITY;               // reference maximum of raw scores of query n
+  st.mc = 0.f;                        // m_ref * c
+  st.l_run = 0.f;                     // this lane's share of the denominator
   const int key_base = tile_begin * BN;
   constexpr int kHalf = 32 * kRowBytes;
 
@@ -396,26 +372,25 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   if (n_t > 1) load_tile<false, NW>(L, 1, k_lds1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  sub_iteration<true, false, false, true, false>(st, st.s_a, st.s_a, qf, k_lds0, nullptr, fo, key_base, n_keys, g,
-                                                 nullptr);
-  sub_iteration<true, false, false, true, false>(st, st.s_b, st.s_b, qf, k_lds0 + kHalf, nullptr, fo, key_base + 32,
-                                                 n_keys, g, nullptr);
-  sub_iteration<false, false, true, false, true>(st, st.s_a, st.s_a, qf, nullptr, nullptr, fo, 0, n_keys, g, &st.s_b);
+  sub_iteration<true, false, false, true>(st, st.s_a, st.s_a, qf, k_lds0, nullptr, fo, key_base, n_keys, g, c, tau);
+  sub_iteration<true, false, false, true>(st, st.s_b, st.s_b, qf, k_lds0 + kHalf, nullptr, fo, key_base + 32, n_keys,
+                                          g, c, tau);
+  sub_iteration<false, false, true, false>(st, st.s_a, st.s_a, qf, nullptr, nullptr, fo, 0, n_keys, g, c, tau);
 
   // ---- steady state: iteration T scores tile T+1 (K) and accumulates tile T (V)
   int T = 0;
   for (; T + 3 < n_t; T += 2) {
-    tile_iteration<NW, false>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g);       // even T
-    tile_iteration<NW, false>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g);   // odd T
+    tile_iteration<NW, false>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);       // even T
+    tile_iteration<NW, false>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g, c, tau);   // odd T
   }
   if (T + 2 < n_t) {
-    tile_iteration<NW, false>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g);
+    tile_iteration<NW, false>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);
     ++T;
   }
   // ---- T == n_t - 2 scores the last tile, which may reach beyond the visible keys
   if (T + 1 < n_t) {
-    if (T & 1) tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g);
-    else tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g);
+    if (T & 1) tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g, c, tau);
+    else tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);
     ++T;
   }
   // ---- drain: T == n_t - 1; last tile's V, last block's softmax
@@ -423,12 +398,11 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const uint8_t* vb = (T & 1) ? v_lds1 : v_lds0;
-    sub_iteration<false, true, true, false, false>(st, st.s_b, st.s_b, qf, nullptr, vb, fo, 0, n_keys, g, nullptr);
-    sub_iteration<false, true, false, false, false>(st, st.s_a, st.s_a, qf, nullptr, vb + kHalf, fo, 0, n_keys, g,
-                                                    nullptr);
+    sub_iteration<false, true, true, false>(st, st.s_b, st.s_b, qf, nullptr, vb, fo, 0, n_keys, g, c, tau);
+    sub_iteration<false, true, false, false>(st, st.s_a, st.s_a, qf, nullptr, vb + kHalf, fo, 0, n_keys, g, c, tau);
   }
   f32x16_t* o_acc = st.o_acc;
-  const float m_log2 = st.m_log2, l_run = st.l_run;
+  const float m_ref = st.m_ref, l_run = st.l_run;
 
   // ---- epilogue.  O^T block db, element i: channel 16*db + 64*(i/8) + 8*((i/4)&1) + 4*g + (i%4)
   const float l_tot = sum_across_halves(l_run);
@@ -447,9 +421,9 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
         w.y = pack_bf16x2(o_acc[db][4 * i4 + 2] * inv_l, o_acc[db][4 * i4 + 3] * inv_l);
         *reinterpret_cast<uint2*>(op + d) = w;
       }
-    if (a.lse && g == 0) a.lse[(int64_t)head * a.n_q + qrow] = m_log2 * 0.69314718056f + logf(l_tot);
+    if (a.lse && g == 0) a.lse[(int64_t)head * a.n_q + qrow] = m_ref * a.scale + logf(l_tot);
   } else {
-    // partial result: unnormalised O (fp32), reference maximum (log2 units) and denominator
+    // partial result: unnormalised O (fp32), reference maximum and denominator
     float* ws = reinterpret_cast<float*>(a.workspace);
     const int64_t row = ((int64_t)split * a.n_heads + head) * a.n_q + qrow;
     float* op = ws + row * kHeadDim;
@@ -463,7 +437,7 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
       }
     if (g == 0) {
       float* ml = ws + (int64_t)sp.n_splits * a.n_heads * a.n_q * kHeadDim + row * 2;
-      ml[0] = m_log2;
+      ml[0] = m_ref;
       ml[1] = l_tot;
     }
   }
@@ -481,13 +455,14 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a, SplitInfo sp) 
   const float* ws = reinterpret_cast<const float*>(a.workspace);
   const int64_t rows = (int64_t)a.n_heads * a.n_q;
   const float* ml = ws + (int64_t)sp.n_splits * rows * kHeadDim;
+  const float c = a.scale * kLog2e;
   float m = -INFINITY;
   for (int s = 0; s < sp.n_splits; ++s) m = fmaxf(m, ml[(s * rows + hq) * 2]);
   float l = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int s = 0; s < sp.n_splits; ++s) {
     const float ms = ml[(s * rows + hq) * 2], ls = ml[(s * rows + hq) * 2 + 1];
-    const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - m);
+    const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((ms - m) * c);
     l += w * ls;
     const float4 o = *reinterpret_cast<const float4*>(ws + (s * rows + hq) * kHeadDim + d4 * 4);
     acc.x += w * o.x; acc.y += w * o.y; acc.z += w * o.z; acc.w += w * o.w;
@@ -497,7 +472,7 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a, SplitInfo sp) 
   wv.x = pack_bf16x2(acc.x * inv, acc.y * inv);
   wv.y = pack_bf16x2(acc.z * inv, acc.w * inv);
   *reinterpret_cast<uint2*>(a.out + (int64_t)q * a.o_tok + (int64_t)head * a.o_head + d4 * 4) = wv;
-  if (a.lse && d4 == 0) a.lse[hq] = m * 0.69314718056f + logf(l);
+  if (a.lse && d4 == 0) a.lse[hq] = m * a.scale + logf(l);
 }
 
 constexpr int kCus = 256;

@@ -1,0 +1,169 @@
+"""Edge cases of the HIP path against the fp64 oracle: many segments, ragged tiles, extreme
+logits, head counts at the limits, far time positions, and the non-default work-group shapes."""
+import os
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2603_06664_amd import workloads as W
+
+import harness as Hn
+
+pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def P():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2603_06664_amd as pkg
+    from paper_2603_06664_amd import binding
+    binding._load()
+    return pkg
+
+
+def _rand_bits(rng, shape, scale=1.0):
+    return W.f32_to_bf16_bits((rng.standard_normal(shape) * scale).astype(np.float32))
+
+
+def _attn_case(P, n_q, H, cap, segs, seed, q_scale=1.0, want_lse=True):
+    import torch
+    import oracle
+    rng = np.random.default_rng(seed)
+    qb, kb, vb = _rand_bits(rng, (n_q, H, 128), q_scale), _rand_bits(rng, (cap, H, 128)), _rand_bits(rng, (cap, H, 128))
+    q, k, v = Hn.to_dev_bf16(qb), Hn.to_dev_bf16(kb), Hn.to_dev_bf16(vb)
+    out = torch.empty_like(q)
+    lse = torch.empty((H, n_q), dtype=torch.float32, device="cuda") if want_lse else None
+    n_keys = sum(n for _, n in segs)
+    wsb = P.chunk_attention_workspace_bytes(n_q, H, n_keys)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    P.chunk_attention(q, n_q, H, k, v, cap, segs, Hn.SCALE, out, lse, ws, wsb)
+    torch.cuda.synchronize()
+    kf, vf = Hn.bits_to_f64(kb), Hn.bits_to_f64(vb)
+    kk = np.concatenate([kf[s:s + n] for s, n in segs])
+    vv = np.concatenate([vf[s:s + n] for s, n in segs])
+    o_ref, lse_ref = oracle.attention(Hn.bits_to_f64(qb), kk, vv, Hn.SCALE)
+    got = Hn.bits_to_f64(Hn.dev_bits(out))
+    return got, o_ref, (lse.cpu().numpy().astype(np.float64) if want_lse else None), lse_ref
+
+
+@pytest.mark.parametrize("segs", [
+    [(300, 70), (0, 33), (100, 129), (250, 5)],     # four segments, all ragged, out of order
+    [(10, 63), (200, 1)],                           # 64 keys split 63 + 1 across a tile
+    [(5, 64), (100, 64), (300, 64)],                # tile-aligned lengths, unaligned starts
+    [(0, 1), (1, 1), (2, 1), (3, 1)],               # four one-key segments
+])
+def test_attention_segment_shapes(P, segs):
+    print("case segs", segs, flush=True)
+    got, ref, lse, lse_ref = _attn_case(P, 77, 3, 400, segs, seed=31)
+    Hn.assert_close("o", got, ref)
+    assert np.max(np.abs(lse - lse_ref)) <= 2e-2
+
+
+@pytest.mark.parametrize("n_q", [1, 31, 32, 33, 127, 129, 255, 257])
+def test_attention_query_counts(P, n_q):
+    print("case n_q", n_q, flush=True)
+    got, ref, lse, lse_ref = _attn_case(P, n_q, 2, 333, [(3, 330)], seed=32 + n_q)
+    Hn.assert_close("o", got, ref)
+    assert np.max(np.abs(lse - lse_ref)) <= 2e-2
+
+
+def test_attention_extreme_logits(P):
+    """Scores spanning hundreds of powers of two: the reference maximum is raised again and
+    again (also by far more than one step), and the softmax saturates.  Scores are exact in
+    fp32 (bf16 inputs, fp32 accumulation), so even here only the bf16 rounding of P and O
+    separates the kernel from the oracle."""
+    for q_scale, seed in ((40.0, 40), (6.0, 42)):
+        got, ref, lse, lse_ref = _attn_case(P, 70, 2, 1000, [(0, 1000)], seed=seed, q_scale=q_scale)
+        assert np.all(np.isfinite(got)) and np.all(np.isfinite(lse))
+        max_abs, rel_l2, _ = Hn.errors(got, ref)
+        print("q_scale %g: max_abs %.3e rel_l2 %.3e" % (q_scale, max_abs, rel_l2), flush=True)
+        Hn.assert_close("o", got, ref)
+        assert np.max(np.abs(lse - lse_ref) / np.maximum(1.0, np.abs(lse_ref))) <= 2e-3
+
+
+def test_attention_increasing_scores(P):
+    """Keys ordered so that later blocks always beat earlier ones (worst case for a lazily
+    raised reference)."""
+    import torch
+    import oracle
+    rng = np.random.default_rng(41)
+    H, n_q, n_k = 1, 40, 640
+    base = rng.standard_normal((1, H, 128)).astype(np.float32)
+    qb = W.f32_to_bf16_bits(np.repeat(base, n_q, axis=0) * 3.0)
+    ramp = np.linspace(-4.0, 4.0, n_k, dtype=np.float32)[:, None, None]
+    kb = W.f32_to_bf16_bits(base * ramp + 0.05 * rng.standard_normal((n_k, H, 128)).astype(np.float32))
+    vb = _rand_bits(rng, (n_k, H, 128))
+    q, k, v = Hn.to_dev_bf16(qb), Hn.to_dev_bf16(kb), Hn.to_dev_bf16(vb)
+    out = torch.empty_like(q)
+    wsb = P.chunk_attention_workspace_bytes(n_q, H, n_k)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    P.chunk_attention(q, n_q, H, k, v, n_k, [(0, n_k)], Hn.SCALE, out, None, ws, wsb)
+    torch.cuda.synchronize()
+    o_ref, _ = oracle.attention(Hn.bits_to_f64(qb), Hn.bits_to_f64(kb), Hn.bits_to_f64(vb), Hn.SCALE)
+    Hn.assert_close("o", Hn.bits_to_f64(Hn.dev_bits(out)), o_ref)
+
+
+@pytest.mark.parametrize("H", [1, 7, 33, 64])
+def test_rope_head_counts(P, H):
+    print("case heads", H, flush=True)
+    cfg = W.ChunkConfig("RH%d" % H, 50 + H, H, 3, 5, start_frame=2, n_frames=2, first_kv_frame=2)
+    inp = W.make_inputs(cfg)
+    for group in (H * 128, 128):
+        ref = Hn.oracle_chain(cfg, inp, norm_group=group)
+        got = Hn.hip_chain(cfg, inp, norm_group=group)
+        Hn.assert_close("q_rot", got["q_rot"], ref["q_rot"])
+        Hn.assert_close("k_cache", got["k_cache"], ref["k_cache"])
+        assert np.array_equal(got["v_cache_bits"], inp.v)
+        Hn.assert_close("o", got["o"], ref["o"])
+
+
+def test_rope_far_time_positions(P):
+    """Frames near the end of a 1024-entry time table: angles of ~1000 rad must still be
+    accurate (they are formed in fp64 when the table is built)."""
+    cfg = W.ChunkConfig("FAR", 61, 2, 4, 6, start_frame=1020, n_frames=3, first_kv_frame=1020)
+    inp = W.make_inputs(cfg)
+    ref = Hn.oracle_chain(cfg, inp)
+    got = Hn.hip_chain(cfg, inp)
+    Hn.assert_close("q_rot", got["q_rot"], ref["q_rot"])
+    Hn.assert_close("k_cache", got["k_cache"], ref["k_cache"])
+
+
+def test_rope_rejects_frame_beyond_table(P):
+    import paper_2603_06664_amd as pkg
+    cfg = W.ChunkConfig("OOR", 62, 2, 4, 6, start_frame=1022, n_frames=3, first_kv_frame=1022)
+    inp = W.make_inputs(cfg)
+    with pytest.raises(pkg.CropeError) as ei:
+        Hn.hip_chain(cfg, inp)
+    assert ei.value.code == -4
+
+
+_VARIANT_SCRIPT = r"""
+import sys, numpy as np
+sys.path.insert(0, %(root)r); sys.path.insert(0, %(root)r + "/tests")
+from paper_2603_06664_amd import workloads as W
+import harness as Hn
+for cfg in (W.ChunkConfig("V1", 71, 3, 9, 11, start_frame=6, n_frames=3, first_kv_frame=0),
+            W.ChunkConfig("V2", 72, 2, 4, 6, start_frame=7, n_frames=1, first_kv_frame=5, cache_frames=3)):
+    inp = W.make_inputs(cfg)
+    ref = Hn.oracle_chain(cfg, inp); got = Hn.hip_chain(cfg, inp)
+    Hn.assert_close("o", got["o"], ref["o"])
+    assert np.max(np.abs(got["lse"] - ref["lse"])) <= 2e-2
+print("variant ok")
+"""
+
+
+@pytest.mark.parametrize("env", [{"CROPE_ATTN_WAVES": "4"}, {"CROPE_ATTN_WAVES": "8"},
+                                 {"CROPE_ATTN_WAVES": "4", "CROPE_ATTN_SPLITS": "3"},
+                                 {"CROPE_ATTN_WAVES": "8", "CROPE_ATTN_SPLITS": "7"}])
+def test_forced_plans_in_a_child_process(env):
+    """The work-group shape and the key split are normally chosen by the library; force the
+    other shapes (the knobs are read once per process, hence the child)."""
+    e = dict(os.environ)
+    e.update(env)
+    r = subprocess.run([sys.executable, "-c", _VARIANT_SCRIPT % {"root": ROOT}], env=e, capture_output=True,
+                       text=True, timeout=110)
+    assert r.returncode == 0 and "variant ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
