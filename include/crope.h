@@ -100,7 +100,8 @@ int crope_build_table(const crope_table_desc* desc, float* d_table, size_t bytes
  *   k_cache,v_cache device bf16 [cache_capacity_tokens][n_heads][128], strides cache_strides
  * Errors: CROPE_ERANGE if any row's t_global >= max_t or dst_token + n_tokens exceeds the
  * capacity; CROPE_EALIGN unless every base pointer and stride*2 bytes is a multiple of 16.
- * n_tokens == 0 is a no-op that returns CROPE_OK.  Input and output buffers must not
+ * n_tokens == 0 is a no-op that returns CROPE_OK; at most 262140 tokens and 64 heads per call.
+ * Input and output buffers must not
  * overlap, except that q_out may alias q. */
 int crope_qk_norm_rotate_append(
     const crope_table_desc* desc, const float* d_table,

@@ -80,6 +80,7 @@ int crope_qk_norm_rotate_append(
   if (!d_table || !q || !k || !v || !gain_q || !gain_k || !q_out || !k_cache || !v_cache)
     return fail(CROPE_EINVAL, "null pointer argument");
   if (n_tokens < 0) return fail(CROPE_EINVAL, "n_tokens is negative");
+  if (n_tokens > 4 * 65535) return fail(CROPE_ERANGE, "more than 262140 tokens in one call");
   if (n_heads <= 0) return fail(CROPE_EINVAL, "n_heads must be positive");
   if (n_heads > crope::rope_max_heads())
     return fail(CROPE_ESHAPE, "n_heads %d exceeds the supported maximum %d", n_heads,

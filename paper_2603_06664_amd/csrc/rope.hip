@@ -66,16 +66,17 @@ __device__ __forceinline__ float group16_sum(float x) {
 // chunks; chunk c is head c/16, channels 8*(c%16)..+7, and c%16 == l%16 for every it, so a
 // lane's four rotation angles are the same for all of its chunks.
 //
-// blockIdx.y selects the tensor a work-group handles (0: q, 1: k, 2: v).  Splitting the
+// blockIdx.x selects the tensor a work-group handles (0: q, 1: k, 2: v; fastest-varying, so
+// the three streams of a token block are dispatched together).  Splitting the
 // three tensors over different waves triples the number of independent load/store streams in
 // flight and lets one wave's stores overlap another's loads; v is a plain copy.
 template <int ITERS>
 __global__ __launch_bounds__(64 * kWavesPerBlock) void rope_kernel(RopeArgs a) {
   const int lane = threadIdx.x & 63;
-  const int tok = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int tok = blockIdx.y * kWavesPerBlock + (threadIdx.x >> 6);
   if (tok >= a.n_tokens) return;
   const int n_chunks = a.n_heads * 16;
-  const int role = blockIdx.y;
+  const int role = blockIdx.x;
   const uint16_t* src = role == 0 ? a.q : role == 1 ? a.k : a.v;
   const int64_t in_base = (int64_t)tok * a.in_tok;
   const int64_t c_base = (a.dst_token + tok) * a.c_tok;
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(64 * kWavesPerBlock) void rope_kernel(RopeArgs a) {
 template <int ITERS>
 hipError_t launch_rope_t(const RopeArgs& a, hipStream_t st) {
   const int blocks = (a.n_tokens + kWavesPerBlock - 1) / kWavesPerBlock;
-  hipLaunchKernelGGL(rope_kernel<ITERS>, dim3(blocks, 3), dim3(64 * kWavesPerBlock), 0, st, a);
+  hipLaunchKernelGGL(rope_kernel<ITERS>, dim3(3, blocks), dim3(64 * kWavesPerBlock), 0, st, a);
   return hipGetLastError();
 }
 

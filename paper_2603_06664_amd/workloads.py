@@ -124,6 +124,12 @@ CONFIGS: Dict[str, ChunkConfig] = {
     # One sequence-parallel rank's share (rank 2 of 8) at 40 heads: rows 1170..1754 of the chunk.
     "C5": ChunkConfig("C5", 4, 40, 30, 52, start_frame=18, n_frames=3, first_kv_frame=0,
                       token_offset=2 * 585, n_local=585),
+    # --- further shapes of the paper's evaluation (Section 4.2.1: 288x512 and 960x1664 next to
+    # 480x832) and the paper's own attention layout after the fused all-to-all (Algorithm 3
+    # step 4: all 4680 queries of the chunk, H/P = 40/8 = 5 heads per rank)
+    "R288": ChunkConfig("R288", 5, 12, 18, 32, start_frame=18, n_frames=3, first_kv_frame=0),
+    "R960": ChunkConfig("R960", 6, 12, 60, 104, start_frame=18, n_frames=3, first_kv_frame=0),
+    "C5P": ChunkConfig("C5P", 7, 5, 30, 52, start_frame=18, n_frames=3, first_kv_frame=0),
 }
 
 

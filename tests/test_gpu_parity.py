@@ -97,7 +97,7 @@ def _sample_rows(n_q, rng, count=40):
     return rows
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "R288", "C5P", "R960"])
 def test_full_size_config(P, name):
     cfg = W.CONFIGS[name]
     _say("case %s: n_q=%d n_keys=%d heads=%d" % (name, cfg.n_q, cfg.n_keys, cfg.n_heads))
