@@ -100,9 +100,9 @@ int crope_build_table(const crope_table_desc* desc, float* d_table, size_t bytes
  *   k_cache,v_cache device bf16 [cache_capacity_tokens][n_heads][128], strides cache_strides
  * Errors: CROPE_ERANGE if any row's t_global >= max_t or dst_token + n_tokens exceeds the
  * capacity; CROPE_EALIGN unless every base pointer and stride*2 bytes is a multiple of 16.
- * n_tokens == 0 is a no-op that returns CROPE_OK; at most 262140 tokens and 64 heads per call.
- * Input and output buffers must not
- * overlap, except that q_out may alias q. */
+ * n_tokens == 0 is a no-op that returns CROPE_OK; at most 262140 tokens and 64 heads per
+ * call (CROPE_ERANGE / CROPE_ESHAPE beyond).  Input and output buffers must not overlap,
+ * except that q_out may alias q. */
 int crope_qk_norm_rotate_append(
     const crope_table_desc* desc, const float* d_table,
     const void* q, const void* k, const void* v, crope_strides in,
@@ -132,7 +132,8 @@ size_t chunk_attention_workspace_bytes(int32_t n_q, int32_t n_heads, int64_t n_k
  *   lse_or_null    device fp32 [n_heads][n_q], natural-log sum-exp of the scaled scores
  *   workspace      device scratch of >= chunk_attention_workspace_bytes(...) bytes, 16-byte
  *                  aligned; may be NULL when that size is 0.  Contents are undefined after.
- * n_q == 0 is a no-op. */
+ * n_q == 0 is a no-op.  Limits (CROPE_ERANGE beyond): cache capacity < 2^31 rows, cache token
+ * stride <= 2^24 elements, at most 2^30 visible keys. */
 int chunk_attention(
     const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
     const void* k_cache, const void* v_cache, crope_strides cache_strides,
