@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "R288", "R960", "C5P"])
+    ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "R288", "R960", "C5P", "C4R"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=1024,
                     help="query rows of the workload the CPU oracle is timed on")

@@ -130,6 +130,9 @@ CONFIGS: Dict[str, ChunkConfig] = {
     "R288": ChunkConfig("R288", 5, 12, 18, 32, start_frame=18, n_frames=3, first_kv_frame=0),
     "R960": ChunkConfig("R960", 6, 12, 60, 104, start_frame=18, n_frames=3, first_kv_frame=0),
     "C5P": ChunkConfig("C5P", 7, 5, 30, 52, start_frame=18, n_frames=3, first_kv_frame=0),
+    # rolling window at full size: a ring of 9 frames (14040 rows) that has wrapped; the final
+    # chunk sees frames 12..20, which sit in slots 3..8, 0, 1, 2 -> two row segments
+    "C4R": ChunkConfig("C4R", 8, 12, 30, 52, start_frame=18, n_frames=3, first_kv_frame=12, cache_frames=9),
 }
 
 

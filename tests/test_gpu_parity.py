@@ -97,7 +97,7 @@ def _sample_rows(n_q, rng, count=40):
     return rows
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "R288", "C5P", "R960"])
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "R288", "C5P", "C4R", "R960"])
 def test_full_size_config(P, name):
     cfg = W.CONFIGS[name]
     _say("case %s: n_q=%d n_keys=%d heads=%d" % (name, cfg.n_q, cfg.n_keys, cfg.n_heads))
@@ -112,7 +112,15 @@ def test_full_size_config(P, name):
     _say("  q_rot   max_abs %.3e rel_l2 %.3e" % e)
     e = Hn.assert_close("k_cache", got["k_cache"], ref["k_cache"], strict_abs=not loose)
     _say("  k_cache max_abs %.3e rel_l2 %.3e" % e)
-    assert np.array_equal(got["v_cache_bits"], inp.v)       # cache rows are in frame order here
+    v_ref = np.zeros_like(got["v_cache_bits"])
+    for (s_, nf, row0, n, off, _) in W.chunk_schedule(cfg):
+        for f in range(nf):      # frame by frame: a ring slot holds one frame
+            lo = max(off, f * cfg.hw)
+            hi = min(off + n, (f + 1) * cfg.hw)
+            if lo < hi:
+                d = W.cache_slot(cfg, s_ + f) * cfg.hw + (lo - f * cfg.hw)
+                v_ref[d:d + hi - lo] = inp.v[row0 + lo - off:row0 + hi - off]
+    assert np.array_equal(got["v_cache_bits"], v_ref)
     e = Hn.assert_close("o", got["o"][rows], ref["o"])
     _say("  o       max_abs %.3e rel_l2 %.3e" % e)
     lse_err = np.max(np.abs(got["lse"][:, rows] - ref["lse"]))
