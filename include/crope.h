@@ -142,6 +142,23 @@ int chunk_attention(
     void* out, crope_strides out_strides, float* lse_or_null,
     void* workspace, size_t workspace_bytes, void* stream);
 
+/* chunk_attention with a per-query prefix limit: query i attends only to the first
+ * q_limit[i] rows of the visible set (rows counted in the order of `segs`).  With keys laid
+ * out in generation order this is the block-causal rule of the generator itself (Section
+ * 3.2: a token attends only to earlier tokens, at the granularity of the generation block of
+ * Section 3.3.2) applied inside ONE call: limit = end of the query's own block reproduces,
+ * in a single pass over a whole sequence, what chunk-by-chunk generation with the cache
+ * computes; limit = i + 1 is token-causal attention.
+ *   q_limit   device int32 [n_q]; values are clamped to [1, total visible rows]
+ * No workspace is needed.  Everything else is as for chunk_attention. */
+int chunk_attention_limited(
+    const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
+    const void* k_cache, const void* v_cache, crope_strides cache_strides,
+    int64_t cache_capacity_tokens,
+    const crope_kv_segment* segs, int32_t n_segs, float scale,
+    const int32_t* q_limit,
+    void* out, crope_strides out_strides, float* lse_or_null, void* stream);
+
 /* Thread-local message describing the last error returned on this thread ("" if none). */
 const char* crope_last_error(void);
 

@@ -91,18 +91,20 @@ struct FragOffsets {
   int v_off[4];
 };
 
-// key0_next: global index of the first key of the block scored by this call (S_{b+1}).
+// key0_next: global index of the first key of the block scored by this call (S_{b+1});
+// lim: this lane's query sees keys [0, lim) (the number of visible keys, or less under a
+// per-query limit).
 template <bool DO_S, bool DO_PV, bool DO_SOFTMAX, bool MASK_S>
 __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_in, f32x16_t& s_out,
                                               const bf16x8_t (&qf)[8],
                                               const uint8_t* k_half,   // K rows of block b+1
                                               const uint8_t* v_half,   // V rows of block b-1
-                                              const FragOffsets& fo, int key0_next, int n_keys, int g,
+                                              const FragOffsets& fo, int key0_next, int lim, int g,
                                               float c, float tau) {
   f32x16_t s_new;
 #pragma unroll
   for (int i = 0; i < 16; ++i)   // keys past the end are masked by seeding their scores with -inf
-    s_new[i] = (MASK_S && key0_next + 8 * (i >> 2) + 4 * g + (i & 3) >= n_keys) ? -INFINITY : 0.f;
+    s_new[i] = (MASK_S && key0_next + 8 * (i >> 2) + 4 * g + (i & 3) >= lim) ? -INFINITY : 0.f;
   uint32_t p_new[8];
   const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
   bf16x8_t pb[2];
@@ -252,22 +254,25 @@ template <int NW, bool MASK_S>
 __device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, const bf16x8_t (&qf)[8],
                                                const FragOffsets& fo, int T, int n_t, uint8_t* k_load,
                                                uint8_t* v_load, const uint8_t* k_read, const uint8_t* v_read,
-                                               int g, float c, float tau) {
+                                               int lim, int g, float c, float tau) {
   constexpr int kHalf = 32 * kRowBytes;
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();   // K_{T+1}, V_T have landed; every wave is done with K_T and V_{T-1}
   if (T + 2 < n_t) load_tile<false, NW>(L, T + 2, k_load);
   load_tile<true, NW>(L, T + 1, v_load);
   sub_iteration<true, true, true, MASK_S>(st, st.s_b, st.s_a, qf, k_read, v_read, fo,
-                                          L.key_first + (2 * T + 2) * 32, L.n_keys, g, c, tau);
+                                          L.key_first + (2 * T + 2) * 32, lim, g, c, tau);
   sub_iteration<true, true, true, MASK_S>(st, st.s_a, st.s_b, qf, k_read + kHalf, v_read + kHalf, fo,
-                                          L.key_first + (2 * T + 3) * 32, L.n_keys, g, c, tau);
+                                          L.key_first + (2 * T + 3) * 32, lim, g, c, tau);
 }
 
 // NW = waves per work-group (4 or 8), each owning 32 queries.  NW = 4: two work-groups per
 // CU.  NW = 8: one work-group per CU, so each K/V tile is copied into LDS once per CU
 // instead of twice, at a coarser query-tile granularity.
-template <int NW>
+// LIMITED: every query carries its own count of leading visible keys (a block-causal or
+// causal prefix mask); every score block is then masked per lane and the key loop stops at the
+// largest limit of the work-group.
+template <int NW, bool LIMITED>
 __global__ __attribute__((amdgpu_flat_work_group_size(64 * NW, 64 * NW), amdgpu_waves_per_eu(2, 2)))
 void attention_kernel(AttnArgs a, SplitInfo sp) {
   constexpr int BM = 32 * NW;   // queries per work-group
@@ -294,7 +299,24 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   const int split = hs % sp.n_splits;
   const int head = hs / sp.n_splits;
   const int q0 = q_tile * BM + wave * 32;
-  const int n_keys = (int)a.n_keys;
+  int n_keys = (int)a.n_keys;
+  int lim = n_keys;   // keys visible to this lane's query
+  if (LIMITED) {
+    const int qrow = min(q0 + n, a.n_q - 1);
+    lim = min(n_keys, max(1, a.q_limit[qrow]));
+    int wmax = lim;
+#pragma unroll
+    for (int m = 16; m >= 1; m >>= 1) wmax = max(wmax, __shfl_xor(wmax, m, 64));
+    // largest limit of the work-group, through the (still unused) first K buffer
+    int* scratch = reinterpret_cast<int*>(k_lds0);
+    if (lane == 0) scratch[wave] = wmax;
+    __syncthreads();
+    int gmax = 1;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) gmax = max(gmax, scratch[w]);
+    __syncthreads();   // everyone has read before the first tile copy overwrites the buffer
+    n_keys = __builtin_amdgcn_readfirstlane(gmax);   // nothing beyond is visible to this work-group
+  }
 
   const int n_tiles_total = (n_keys + BN - 1) / BN;
   const int tile_begin = split * sp.tiles_per_split;
@@ -372,25 +394,25 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   if (n_t > 1) load_tile<false, NW>(L, 1, k_lds1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  sub_iteration<true, false, false, true>(st, st.s_a, st.s_a, qf, k_lds0, nullptr, fo, key_base, n_keys, g, c, tau);
-  sub_iteration<true, false, false, true>(st, st.s_b, st.s_b, qf, k_lds0 + kHalf, nullptr, fo, key_base + 32, n_keys,
+  sub_iteration<true, false, false, true>(st, st.s_a, st.s_a, qf, k_lds0, nullptr, fo, key_base, lim, g, c, tau);
+  sub_iteration<true, false, false, true>(st, st.s_b, st.s_b, qf, k_lds0 + kHalf, nullptr, fo, key_base + 32, lim,
                                           g, c, tau);
-  sub_iteration<false, false, true, false>(st, st.s_a, st.s_a, qf, nullptr, nullptr, fo, 0, n_keys, g, c, tau);
+  sub_iteration<false, false, true, false>(st, st.s_a, st.s_a, qf, nullptr, nullptr, fo, 0, lim, g, c, tau);
 
   // ---- steady state: iteration T scores tile T+1 (K) and accumulates tile T (V)
   int T = 0;
   for (; T + 3 < n_t; T += 2) {
-    tile_iteration<NW, false>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);       // even T
-    tile_iteration<NW, false>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g, c, tau);   // odd T
+    tile_iteration<NW, LIMITED>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);       // even T
+    tile_iteration<NW, LIMITED>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, lim, g, c, tau);   // odd T
   }
   if (T + 2 < n_t) {
-    tile_iteration<NW, false>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);
+    tile_iteration<NW, LIMITED>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);
     ++T;
   }
   // ---- T == n_t - 2 scores the last tile, which may reach beyond the visible keys
   if (T + 1 < n_t) {
-    if (T & 1) tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds1, v_lds0, k_lds0, v_lds1, g, c, tau);
-    else tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, g, c, tau);
+    if (T & 1) tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds1, v_lds0, k_lds0, v_lds1, lim, g, c, tau);
+    else tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);
     ++T;
   }
   // ---- drain: T == n_t - 1; last tile's V, last block's softmax
@@ -398,8 +420,8 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const uint8_t* vb = (T & 1) ? v_lds1 : v_lds0;
-    sub_iteration<false, true, true, false>(st, st.s_b, st.s_b, qf, nullptr, vb, fo, 0, n_keys, g, c, tau);
-    sub_iteration<false, true, false, false>(st, st.s_a, st.s_a, qf, nullptr, vb + kHalf, fo, 0, n_keys, g, c, tau);
+    sub_iteration<false, true, true, false>(st, st.s_b, st.s_b, qf, nullptr, vb, fo, 0, lim, g, c, tau);
+    sub_iteration<false, true, false, false>(st, st.s_a, st.s_a, qf, nullptr, vb + kHalf, fo, 0, lim, g, c, tau);
   }
   f32x16_t* o_acc = st.o_acc;
   const float m_ref = st.m_ref, l_run = st.l_run;
@@ -518,14 +540,14 @@ Plan choose_plan(int n_q, int n_heads, int64_t n_keys) {
   return best;
 }
 
-template <int NW>
+template <int NW, bool LIMITED>
 hipError_t launch_attention_t(const AttnArgs& a, SplitInfo sp, hipStream_t st) {
   sp.q_tiles = (a.n_q + 32 * NW - 1) / (32 * NW);
   const int64_t total_units = (int64_t)sp.q_tiles * a.n_heads * sp.n_splits;
   if (total_units > (1 << 30)) return hipErrorInvalidValue;
   sp.total_units = (int)total_units;
   sp.units_per_xcd = (sp.total_units + kXcds - 1) / kXcds;
-  hipLaunchKernelGGL(attention_kernel<NW>, dim3(kXcds * sp.units_per_xcd), dim3(64 * NW), 0, st, a, sp);
+  hipLaunchKernelGGL((attention_kernel<NW, LIMITED>), dim3(kXcds * sp.units_per_xcd), dim3(64 * NW), 0, st, a, sp);
   return hipGetLastError();
 }
 
@@ -538,12 +560,15 @@ size_t attention_workspace_bytes(int n_q, int n_heads, int64_t n_keys) {
 }
 
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
-  const Plan plan = choose_plan(a.n_q, a.n_heads, a.n_keys);
+  Plan plan = choose_plan(a.n_q, a.n_heads, a.n_keys);
+  if (a.q_limit) plan.splits = 1;   // the per-query limits already shorten the key loops
   SplitInfo sp;
   sp.n_splits = plan.splits;
   const int n_tiles = (int)((a.n_keys + BN - 1) / BN);
   sp.tiles_per_split = (n_tiles + sp.n_splits - 1) / sp.n_splits;
-  hipError_t e = plan.waves == 8 ? launch_attention_t<8>(a, sp, st) : launch_attention_t<4>(a, sp, st);
+  hipError_t e;
+  if (a.q_limit) e = plan.waves == 8 ? launch_attention_t<8, true>(a, sp, st) : launch_attention_t<4, true>(a, sp, st);
+  else e = plan.waves == 8 ? launch_attention_t<8, false>(a, sp, st) : launch_attention_t<4, false>(a, sp, st);
   if (e != hipSuccess || sp.n_splits == 1) return e;
   const int64_t total = (int64_t)a.n_heads * a.n_q * (kHeadDim / 4);
   hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, sp);

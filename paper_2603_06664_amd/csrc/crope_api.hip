@@ -141,11 +141,17 @@ size_t chunk_attention_workspace_bytes(int32_t n_q, int32_t n_heads, int64_t n_k
   return crope::attention_workspace_bytes(n_q, n_heads, n_keys);
 }
 
-int chunk_attention(const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
-                    const void* k_cache, const void* v_cache, crope_strides cache_strides,
-                    int64_t cache_capacity_tokens, const crope_kv_segment* segs, int32_t n_segs,
-                    float scale, void* out, crope_strides out_strides, float* lse_or_null,
-                    void* workspace, size_t workspace_bytes, void* stream) {
+}  // extern "C"
+#pragma GCC visibility pop
+
+namespace {
+int attention_impl(const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
+                   const void* k_cache, const void* v_cache, crope_strides cache_strides,
+                   int64_t cache_capacity_tokens, const crope_kv_segment* segs, int32_t n_segs,
+                   float scale, const int32_t* q_limit, bool limited, void* out, crope_strides out_strides,
+                   float* lse_or_null, void* workspace, size_t workspace_bytes, void* stream) {
+  if (limited && !q_limit) return fail(CROPE_EINVAL, "q_limit is null");
+  if (limited && ((uintptr_t)q_limit & 3)) return fail(CROPE_EALIGN, "q_limit is not 4-byte aligned");
   if (!q || !k_cache || !v_cache || !out || !segs)
     return fail(CROPE_EINVAL, "null pointer argument");
   if (n_q < 0) return fail(CROPE_EINVAL, "n_q is negative");
@@ -179,13 +185,14 @@ int chunk_attention(const void* q, crope_strides q_strides, int32_t n_q, int32_t
     a.segs.end[i] = (int32_t)n_keys;
   }
   for (int i = n_segs; i < crope::kMaxSegments; ++i) a.segs.base[i] = a.segs.base[n_segs - 1];
-  const size_t need = crope::attention_workspace_bytes(n_q > 0 ? n_q : 1, n_heads, n_keys);
+  const size_t need = limited ? 0 : crope::attention_workspace_bytes(n_q > 0 ? n_q : 1, n_heads, n_keys);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(CROPE_EWORKSPACE, "workspace has %zu bytes, needs %zu", workspace ? workspace_bytes : 0,
                 need);
   if (n_q == 0) { g_err[0] = 0; return CROPE_OK; }
   a.q = (const uint16_t*)q; a.q_tok = q_strides.token; a.q_head = q_strides.head;
   a.n_q = n_q; a.n_heads = n_heads;
+  a.q_limit = limited ? q_limit : nullptr;
   a.k_cache = (const uint16_t*)k_cache; a.v_cache = (const uint16_t*)v_cache;
   a.c_tok = cache_strides.token; a.c_head = cache_strides.head;
   a.n_keys = n_keys; a.scale = scale;
@@ -195,6 +202,29 @@ int chunk_attention(const void* q, crope_strides q_strides, int32_t n_q, int32_t
   if (e != hipSuccess) return hip_fail(e, "chunk_attention launch");
   g_err[0] = 0;
   return CROPE_OK;
+}
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+int chunk_attention(const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
+                    const void* k_cache, const void* v_cache, crope_strides cache_strides,
+                    int64_t cache_capacity_tokens, const crope_kv_segment* segs, int32_t n_segs,
+                    float scale, void* out, crope_strides out_strides, float* lse_or_null,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  return attention_impl(q, q_strides, n_q, n_heads, k_cache, v_cache, cache_strides, cache_capacity_tokens,
+                        segs, n_segs, scale, nullptr, false, out, out_strides, lse_or_null, workspace,
+                        workspace_bytes, stream);
+}
+
+int chunk_attention_limited(const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
+                            const void* k_cache, const void* v_cache, crope_strides cache_strides,
+                            int64_t cache_capacity_tokens, const crope_kv_segment* segs, int32_t n_segs,
+                            float scale, const int32_t* q_limit, void* out, crope_strides out_strides,
+                            float* lse_or_null, void* stream) {
+  return attention_impl(q, q_strides, n_q, n_heads, k_cache, v_cache, cache_strides, cache_capacity_tokens,
+                        segs, n_segs, scale, q_limit, true, out, out_strides, lse_or_null, nullptr, 0, stream);
 }
 
 }  // extern "C"

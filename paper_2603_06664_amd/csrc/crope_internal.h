@@ -51,6 +51,7 @@ struct Segments {
 struct AttnArgs {
   const uint16_t* q; int64_t q_tok, q_head;
   int n_q, n_heads;
+  const int32_t* q_limit;   // optional: query i sees only the first q_limit[i] visible keys
   const uint16_t *k_cache, *v_cache; int64_t c_tok, c_head;
   Segments segs; int64_t n_keys;
   float scale;

@@ -167,3 +167,75 @@ def test_forced_plans_in_a_child_process(env):
     r = subprocess.run([sys.executable, "-c", _VARIANT_SCRIPT % {"root": ROOT}], env=e, capture_output=True,
                        text=True, timeout=110)
     assert r.returncode == 0 and "variant ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
+def _limited_case(P, n_q, H, n_k, limits, seed):
+    import torch
+    import oracle
+    rng = np.random.default_rng(seed)
+    qb, kb, vb = _rand_bits(rng, (n_q, H, 128)), _rand_bits(rng, (n_k, H, 128)), _rand_bits(rng, (n_k, H, 128))
+    q, k, v = Hn.to_dev_bf16(qb), Hn.to_dev_bf16(kb), Hn.to_dev_bf16(vb)
+    out = torch.empty_like(q)
+    lse = torch.empty((H, n_q), dtype=torch.float32, device="cuda")
+    lim = torch.from_numpy(np.asarray(limits, dtype=np.int32)).cuda()
+    P.chunk_attention_limited(q, n_q, H, k, v, n_k, [(0, n_k)], Hn.SCALE, lim, out, lse)
+    torch.cuda.synchronize()
+    # oracle: key m visible to query i iff m < limit_i  <=>  k_block[m] = m <= q_block[i] = limit_i - 1
+    lim_c = np.clip(np.asarray(limits), 1, n_k)
+    o_ref, lse_ref = oracle.attention(Hn.bits_to_f64(qb), Hn.bits_to_f64(kb), Hn.bits_to_f64(vb), Hn.SCALE,
+                                      q_block=(lim_c - 1).astype(np.int32), k_block=np.arange(n_k, dtype=np.int32))
+    return Hn.bits_to_f64(Hn.dev_bits(out)), o_ref, lse.cpu().numpy().astype(np.float64), lse_ref
+
+
+@pytest.mark.parametrize("kind", ["block_causal", "token_causal", "ragged", "clamped"])
+def test_attention_with_per_query_limits(P, kind):
+    """One pass over a whole sequence with the generator's block-causal rule (and other prefix
+    masks) against the oracle's masked attention."""
+    print("case", kind, flush=True)
+    n = 600
+    i = np.arange(n)
+    if kind == "block_causal":
+        limits = (i // 150 + 1) * 150          # blocks of 150 tokens: query sees up to the end of its block
+    elif kind == "token_causal":
+        limits = i + 1
+    elif kind == "ragged":
+        limits = np.random.default_rng(7).integers(1, n + 1, size=n)
+    else:
+        limits = np.where(i % 2 == 0, 0, 10 * n)   # out-of-range values are clamped to [1, n]
+    got, ref, lse, lse_ref = _limited_case(P, n, 3, n, limits, seed=80)
+    Hn.assert_close("o", got, ref)
+    assert np.max(np.abs(lse - lse_ref)) <= 2e-2
+
+
+def test_one_shot_block_causal_equals_streaming_on_gpu(P):
+    """Streaming == one-shot on the device: generating three blocks one at a time with the
+    cache gives the same outputs as ONE limited call over the whole sequence."""
+    import torch
+    cfg_blocks = [W.ChunkConfig("OS%d" % b, 90, 3, 6, 8, start_frame=3 * b, n_frames=3, first_kv_frame=0)
+                  for b in range(3)]
+    last = cfg_blocks[-1]
+    inp = W.make_inputs(last)                   # k, v for all 9 frames; q for the last block only
+    rng = np.random.default_rng(91)
+    hw, H = last.hw, last.n_heads
+    q_all = W.f32_to_bf16_bits(rng.standard_normal((9 * hw, H, 128), dtype=np.float32))
+    streamed = []
+    for b, cfg in enumerate(cfg_blocks):
+        sub = W.ChunkInputs(cfg, q_all[3 * b * hw:3 * (b + 1) * hw], inp.k[:3 * (b + 1) * hw],
+                            inp.v[:3 * (b + 1) * hw], inp.gain_q, inp.gain_k)
+        streamed.append(Hn.hip_chain(cfg, sub)["o"])
+    streamed = np.concatenate(streamed, axis=0)
+    # one shot: rotate everything with s = 0, then one limited attention call
+    desc, tab = Hn.make_table()
+    n = 9 * hw
+    q, k, v = Hn.to_dev_bf16(q_all), Hn.to_dev_bf16(inp.k), Hn.to_dev_bf16(inp.v)
+    gq, gk = torch.from_numpy(inp.gain_q).cuda(), torch.from_numpy(inp.gain_k).cuda()
+    qo, kc, vc = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    P.crope_qk_norm_rotate_append(desc, tab, q, k, v, gq, gk, 1e-6, H * 128, n, H, last.grid_h, last.grid_w,
+                                  0, 0, qo, kc, vc, n, 0)
+    limits = torch.from_numpy(((np.arange(n) // (3 * hw) + 1) * 3 * hw).astype(np.int32)).cuda()
+    out = torch.empty_like(qo)
+    P.chunk_attention_limited(qo, n, H, kc, vc, n, [(0, n)], Hn.SCALE, limits, out)
+    torch.cuda.synchronize()
+    one_shot = Hn.bits_to_f64(Hn.dev_bits(out))
+    # both sides are bf16 results of the same exact scores; they differ by rounding order only
+    Hn.assert_close("one-shot vs streamed", one_shot, streamed)
