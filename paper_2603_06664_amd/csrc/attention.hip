@@ -10,12 +10,12 @@
 // fetched in that same order with the transposing LDS read (ds_read_b64_tr_b16) from the
 // row-major V tile.
 //
-// A work-group is 4 waves (128 queries of one head); two work-groups share a CU so that one
-// wave's softmax (VALU) overlaps the other's MFMAs.  K and V tiles of 64 keys are copied
-// HBM -> LDS without passing through registers (global_load_lds, 16 B per lane), double
-// buffered, XOR-swizzled by choosing which global chunk each lane fetches.
+// A work-group is 4 or 8 waves (128 or 256 queries of one head), always two waves per SIMD:
+// a wave's own VALU work does not overlap its own MFMAs on this hardware, only another
+// wave's does.  K and V tiles of 64 keys are copied HBM -> LDS without passing through
+// registers (global_load_lds, 16 B per lane), double buffered, XOR-swizzled by choosing
+// which global chunk each lane fetches.
 #include <cstdlib>
-#include <type_traits>
 #include "crope_internal.h"
 
 namespace crope {
@@ -51,7 +51,7 @@ constexpr int BN = 64;                  // keys per tile
 constexpr int kRowBytes = kHeadDim * 2; // 256 B per key row in LDS (swizzled, unpadded)
 constexpr int kTileBytes = BN * kRowBytes;   // 16 KB
 constexpr float kLog2e = 1.44269504088896340736f;
-// A query's reference maximum is only raised when a tile's maximum exceeds it by more than
+// A query's reference maximum is only raised when a block's maximum exceeds it by more than
 // this many powers of two; until then probabilities may exceed 1 (at most 2^8), which fp32
 // accumulators and bf16's exponent range absorb, and the O rescale is skipped.
 constexpr float kRescaleLog2 = 8.0f;
