@@ -186,3 +186,25 @@ def test_ring_wrap_equals_sliding_window_reference():
         hi = (b + 1) * hw
         ref, _ = oracle.attention(qr[b * hw:hi], kr[lo:hi], v[lo:hi], SCALE)
         assert np.max(np.abs(ring[b * hw:hi] - ref)) < 1e-12
+
+
+def test_c1_oracle_values_are_stable():
+    """Regression pin: sampled oracle outputs for configuration C1 match the stored values
+    (written by tests/golden/make_c1_golden.py, which calls only the oracle)."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(__file__), "golden")
+    spec = importlib.util.spec_from_file_location("make_c1_golden", os.path.join(here, "make_c1_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    q_rot, k_rot, o, lse = mod.c1_outputs()
+    arrays = dict(q_rot=q_rot, k_rot=k_rot, o=o, lse=lse)
+    n = 0
+    for ln in open(os.path.join(here, "c1_oracle_values.txt")):
+        if ln.startswith("#") or not ln.strip():
+            continue
+        parts = ln.split()
+        idx = tuple(int(x) for x in parts[1:-1])
+        assert arrays[parts[0]][idx] == pytest.approx(float(parts[-1]), rel=1e-12, abs=1e-14)
+        n += 1
+    assert n == 15
