@@ -35,8 +35,9 @@ def _load():
                                       ctypes.c_int, ctypes.c_int64, _D]
         lib.oracle_attention.argtypes = [_D, _D, _D, ctypes.c_int64, ctypes.c_int64, ctypes.c_int,
                                          ctypes.c_int, ctypes.c_double, _I, _I, _D, _D, _D]
+        lib.oracle_project.argtypes = [_D, _D, _D, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, _D]
         for f in (lib.oracle_axis_table, lib.oracle_decode, lib.oracle_rmsnorm, lib.oracle_rotate,
-                  lib.oracle_attention):
+                  lib.oracle_attention, lib.oracle_project):
             f.restype = None
         _lib = lib
     return _lib
@@ -97,6 +98,35 @@ def rotate(x, dims: Sequence[int], theta: float, grid_h: int, grid_w: int, s: in
 def qk_norm_rotate(x, gain, eps, group, dims, theta, grid_h, grid_w, s, delta=0) -> np.ndarray:
     """RMSNorm then rotation, no rounding in between."""
     return rotate(rmsnorm(x, gain, eps, group), dims, theta, grid_h, grid_w, s, delta)
+
+
+def project(x, w, bias=None) -> np.ndarray:
+    """x: [n, C]; w: [O, C] (a linear layer's [out][in] weights); bias: [O] or None -> [n, O]."""
+    x, w = _f64(x), _f64(w)
+    n, c_in = x.shape
+    n_out = w.shape[0]
+    assert w.shape == (n_out, c_in)
+    b = None if bias is None else _f64(bias).reshape(-1)
+    assert b is None or b.size == n_out
+    y = np.empty((n, n_out), dtype=np.float64)
+    _load().oracle_project(_dp(x), _dp(w), _dp(b) if b is not None else None, n, c_in, n_out, _dp(y))
+    return y
+
+
+def qkv_project_norm_rotate(x, w, bias, gain_q, gain_k, eps, group, n_heads, dims, theta, grid_h,
+                            grid_w, s, delta=0):
+    """Algorithm 3 steps 1-3 with nothing rounded in between: project, split the output
+    columns into q | k | v, RMS-normalise and rotate q and k.  Returns (q~, k~, v), each
+    [n, H, D]."""
+    y = project(x, w, bias)
+    n = y.shape[0]
+    hd = y.shape[1] // 3
+    D = hd // n_heads
+    q = y[:, :hd].reshape(n, n_heads, D)
+    k = y[:, hd:2 * hd].reshape(n, n_heads, D)
+    v = y[:, 2 * hd:].reshape(n, n_heads, D).copy()
+    return (qk_norm_rotate(q, gain_q, eps, group, dims, theta, grid_h, grid_w, s, delta),
+            qk_norm_rotate(k, gain_k, eps, group, dims, theta, grid_h, grid_w, s, delta), v)
 
 
 def attention(q, k, v, scale: float, q_block: Optional[np.ndarray] = None,

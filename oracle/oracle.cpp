@@ -13,7 +13,8 @@
 // numpy.unravel_index, norm preservation, identity at the origin, the relative-position
 // identity, a complex-number re-derivation of the rotation that follows Algorithm 2,
 // library softmax-attention in fp64, row sums, permutation invariance, and streaming ==
-// one-shot block-causal attention.  End-to-end numeric values are not printed anywhere in
+// one-shot block-causal attention; for the projection: a library matmul, an identity
+// weight (projection == its input), a zero input (projection == bias) and linearity.  End-to-end numeric values are not printed anywhere in
 // the paper, so there is no printed-value pin ("parity unpinned by printed values").
 #include <cmath>
 #include <cstdint>
@@ -155,6 +156,20 @@ void oracle_attention(const double* q, const double* k, const double* v, int64_t
       if (lse) lse[(size_t)head * Lq + i] = M + std::log(Z);
     }
   }
+}
+
+// Algorithm 3 step 1, the local QKV projection: y[i][o] = sum_c x[i][c] * w[o][c] + bias[o]
+// (weights stored [out][in] like a linear layer; bias may be null).  Columns 0..HD-1 of y
+// are q, the next HD are k, the last HD are v.
+void oracle_project(const double* x, const double* w, const double* bias, int64_t n, int64_t c_in,
+                    int64_t n_out, double* y) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i)
+    for (int64_t o = 0; o < n_out; ++o) {
+      double acc = 0.0;
+      for (int64_t c = 0; c < c_in; ++c) acc += x[i * c_in + c] * w[o * c_in + c];
+      y[i * n_out + o] = acc + (bias ? bias[o] : 0.0);
+    }
 }
 
 }  // extern "C"

@@ -195,3 +195,27 @@ def cache_slot(cfg: ChunkConfig, frame: int) -> int:
     """Ring slot (in frames) that holds global frame ``frame``."""
     return (frame - cfg.first_kv_frame) % cfg.capacity_frames if cfg.cache_frames is None \
         else frame % cfg.capacity_frames
+
+
+# --------------------------------------------------------------------------- projection
+@dataclass
+class ProjectionInputs:
+    """Inputs of the local QKV projection (Algorithm 3 step 1) for one call's token rows."""
+    x: np.ndarray      # [n_tokens, c_in] uint16 (bf16 bits): hidden states
+    w: np.ndarray      # [3*H*D, c_in] uint16 (bf16 bits): rows 0..HD-1 W_q, then W_k, then W_v
+    bias: np.ndarray   # [3*H*D] float32, bf16-representable
+
+
+def make_projection_inputs(cfg: ChunkConfig, n_tokens: Optional[int] = None,
+                           c_in: Optional[int] = None) -> ProjectionInputs:
+    """Draw order with ``default_rng(cfg.seed + 1000)``: x ~ N(0,1) [n, c_in]; w ~ N(0, 1/c_in)
+    [3HD, c_in] (so that the projected q, k, v are ~N(0,1) like the unfused path's inputs);
+    bias ~ N(0, 0.1) [3HD].  c_in defaults to the model width H*D."""
+    rng = np.random.default_rng(cfg.seed + 1000)
+    hd = cfg.n_heads * cfg.head_dim
+    c_in = hd if c_in is None else c_in
+    n = cfg.n_q if n_tokens is None else n_tokens
+    x = f32_to_bf16_bits(rng.standard_normal((n, c_in), dtype=np.float32))
+    w = f32_to_bf16_bits(rng.standard_normal((3 * hd, c_in), dtype=np.float32) * np.float32(c_in ** -0.5))
+    bias = round_to_bf16((0.1 * rng.standard_normal(3 * hd, dtype=np.float32)).astype(np.float32))
+    return ProjectionInputs(x, w, bias)
