@@ -159,6 +159,43 @@ int chunk_attention_limited(
     const int32_t* q_limit,
     void* out, crope_strides out_strides, float* lse_or_null, void* stream);
 
+/* Bytes of scratch crope_qkv_project_norm_rotate_append needs (0 for norm_group == 128). */
+size_t crope_qkv_project_workspace_bytes(int32_t n_tokens, int32_t n_heads, int32_t norm_group);
+
+/* Local QKV projection fused with crope_qk_norm_rotate_append (Algorithm 3 steps 1, 2, 3 and
+ * 5 in one call; the projection + RoPE operator fusion of Section 3.4.1 item 3).
+ *
+ * y[i][o] = sum_c x[i][c] * w_qkv[o][c] + bias[o] (bf16 products, fp32 accumulation); columns
+ * [0, HD) of y are q, [HD, 2HD) k, [2HD, 3HD) v, HD = n_heads*128, head h = columns
+ * h*128..h*128+127 of each.  q and k are then normalised, rotated and stored, and v stored,
+ * exactly as crope_qk_norm_rotate_append does, but from the fp32 accumulators: y is never
+ * rounded to bf16.  With norm_group == 128 every output is rounded once.  With norm_group ==
+ * n_heads*128 the 1/rms factor of a token is only known once all heads are done, so q and k
+ * are stored as rotate(gain*y) and multiplied by 1/rms in place by a second pass (two
+ * roundings; error at most 2^-8 relative).
+ *
+ *   x              device bf16 [n_tokens][c_in], row stride x_token_stride elements
+ *   w_qkv          device bf16 [3*n_heads*128][c_in], contiguous ([out][in] like a linear layer)
+ *   bias_or_null   device fp32 [3*n_heads*128]
+ *   c_in           reduction length, a positive multiple of 64
+ *   workspace      device, >= crope_qkv_project_workspace_bytes(...) bytes, 16-byte aligned; may
+ *                  be NULL when that size is 0.  Contents are undefined afterwards.
+ * Everything else, and every error, as for crope_qk_norm_rotate_append; additionally
+ * CROPE_ESHAPE if c_in is not a positive multiple of 64, CROPE_ERANGE if x_token_stride
+ * exceeds 2^24, CROPE_EWORKSPACE if the workspace is missing or too small.  x and w_qkv must
+ * not overlap any output. */
+int crope_qkv_project_norm_rotate_append(
+    const crope_table_desc* desc, const float* d_table,
+    const void* x, int64_t x_token_stride, const void* w_qkv, const float* bias_or_null,
+    int32_t c_in,
+    const float* gain_q, const float* gain_k, float eps, int32_t norm_group,
+    int32_t n_tokens, int32_t n_heads, int32_t grid_h, int32_t grid_w,
+    int32_t start_frame, int32_t token_offset,
+    void* q_out, crope_strides q_out_strides,
+    void* k_cache, void* v_cache, crope_strides cache_strides,
+    int64_t cache_capacity_tokens, int64_t dst_token,
+    void* workspace, size_t workspace_bytes, void* stream);
+
 /* Thread-local message describing the last error returned on this thread ("" if none). */
 const char* crope_last_error(void);
 

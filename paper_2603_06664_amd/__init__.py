@@ -7,5 +7,6 @@ if it cannot.
 """
 from .binding import (  # noqa: F401
     CropeError, TableDesc, chunk_attention, chunk_attention_limited, chunk_attention_workspace_bytes, crope_build_table,
-    crope_last_error, crope_qk_norm_rotate_append, crope_table_bytes, crope_version, library_path,
+    crope_last_error, crope_qk_norm_rotate_append, crope_qkv_project_norm_rotate_append,
+    crope_qkv_project_workspace_bytes, crope_table_bytes, crope_version, library_path,
 )

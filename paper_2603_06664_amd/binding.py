@@ -93,6 +93,12 @@ def _load():
     lib.chunk_attention_limited.argtypes = [
         vp, _Strides, i32, i32, vp, vp, _Strides, i64, ctypes.POINTER(_Segment), i32, f32, vp, vp,
         _Strides, vp, vp]
+    lib.crope_qkv_project_workspace_bytes.restype = ctypes.c_size_t
+    lib.crope_qkv_project_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.crope_qkv_project_norm_rotate_append.restype = ctypes.c_int
+    lib.crope_qkv_project_norm_rotate_append.argtypes = [
+        ctypes.POINTER(_Desc), vp, vp, i64, vp, vp, i32, vp, vp, f32, i32, i32, i32, i32, i32, i32,
+        i32, vp, _Strides, vp, vp, _Strides, i64, i64, vp, ctypes.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -193,3 +199,30 @@ def chunk_attention_limited(q, n_q: int, n_heads: int, k_cache, v_cache, cache_c
     _check(_load().chunk_attention_limited(
         _ptr(q), _strides(q), n_q, n_heads, _ptr(k_cache), _ptr(v_cache), sc, cache_capacity_tokens,
         arr, len(segs), scale, _ptr(q_limit), _ptr(out), _strides(out), _ptr(lse), _stream(stream)))
+
+
+def crope_qkv_project_workspace_bytes(n_tokens: int, n_heads: int, norm_group: int) -> int:
+    return int(_load().crope_qkv_project_workspace_bytes(n_tokens, n_heads, norm_group))
+
+
+def crope_qkv_project_norm_rotate_append(desc: TableDesc, d_table, x, w_qkv, bias, c_in: int, gain_q,
+                                         gain_k, eps: float, norm_group: int, n_tokens: int,
+                                         n_heads: int, grid_h: int, grid_w: int, start_frame: int,
+                                         token_offset: int, q_out, k_cache, v_cache,
+                                         cache_capacity_tokens: int, dst_token: int, workspace=None,
+                                         workspace_bytes: int = 0, stream=None) -> None:
+    d = desc._c()
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise CropeError(CROPE_EINVAL, "expected x as [token, c_in] with contiguous channels")
+    if w_qkv.dim() != 2 or not w_qkv.is_contiguous():
+        raise CropeError(CROPE_EINVAL, "expected w_qkv as a contiguous [3*H*128, c_in] tensor")
+    sc = _strides(k_cache)
+    if _strides(v_cache).token != sc.token or _strides(v_cache).head != sc.head:
+        raise CropeError(CROPE_EINVAL, "k_cache and v_cache must share strides")
+    if workspace is not None and workspace_bytes == 0:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    _check(_load().crope_qkv_project_norm_rotate_append(
+        ctypes.byref(d), _ptr(d_table), _ptr(x), int(x.stride(0)), _ptr(w_qkv), _ptr(bias), c_in,
+        _ptr(gain_q), _ptr(gain_k), eps, norm_group, n_tokens, n_heads, grid_h, grid_w, start_frame,
+        token_offset, _ptr(q_out), _strides(q_out), _ptr(k_cache), _ptr(v_cache), sc,
+        cache_capacity_tokens, dst_token, _ptr(workspace), workspace_bytes, _stream(stream)))

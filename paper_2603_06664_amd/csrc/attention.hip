@@ -213,6 +213,25 @@ struct Loader {     // scalars only, so that it is promoted to registers at once
   uint32_t k_lane_off, v_lane_off;         // row0 * row_bytes + chunk offset
 };
 
+// 16 bytes per lane, HBM -> LDS without passing through registers: lane i's data lands at
+// LDS address lds_dst + 16*i (the LDS base travels in M0).  Written as inline assembly, not
+// with the compiler's builtin: while a builtin copy is in flight the compiler's wait-count
+// insertion turns every later "wait for this LDS read" into "wait for ALL LDS reads", which
+// exposes the full LDS latency at each MFMA that consumes a fragment.  The copies are
+// waited for explicitly (s_waitcnt vmcnt) before the barrier that publishes a tile.
+#define LDS_ADDR(p) ((uint32_t)(uintptr_t)((__attribute__((address_space(3))) void*)(p)))
+__device__ __forceinline__ void copy16_uniform(const uint8_t* base /* wave-uniform */, uint32_t lane_off,
+                                               uint8_t* lds_dst /* wave-uniform */) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(LDS_ADDR(lds_dst));
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(lane_off), "s"(base), "s"(m0) : "memory");
+}
+__device__ __forceinline__ void copy16_per_lane(const uint8_t* src, uint8_t* lds_dst /* wave-uniform */) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(LDS_ADDR(lds_dst));
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(src), "s"(m0) : "memory");
+}
+
 __device__ __forceinline__ int seg_row(const Loader& L, int vk) {
   // arithmetic select (no value select the compiler could turn into a table lookup)
   return vk + L.seg_base3 + (vk < L.seg_end2 ? L.d2 : 0) + (vk < L.seg_end1 ? L.d1 : 0) +
@@ -232,8 +251,7 @@ __device__ __forceinline__ void load_tile(const Loader& L, int tile, uint8_t* ds
     const uint32_t lane_off = IS_V ? L.v_lane_off : L.k_lane_off;
 #pragma unroll
     for (int t = 0; t < 16 / NW; ++t)
-      __builtin_amdgcn_global_load_lds(GLB_PTR(base + (int64_t)(4 * NW * t) * L.row_bytes + lane_off),
-                                       LDS_PTR(dst + t * 4 * NW * kRowBytes), 16, 0, 0);
+      copy16_uniform(base + (int64_t)(4 * NW * t) * L.row_bytes, lane_off, dst + t * 4 * NW * kRowBytes);
   } else {
     // tile straddles a segment boundary or the end of the keys: per-lane row lookup; rows
     // past the end re-read the last key (their scores are masked)
@@ -242,7 +260,7 @@ __device__ __forceinline__ void load_tile(const Loader& L, int tile, uint8_t* ds
       const int vk = min(k_first + L.row0 + 4 * NW * t, L.n_keys - 1);
       const uint8_t* src = head + (int64_t)seg_row(L, vk) * L.row_bytes +
                            (IS_V ? L.v_chunk_bytes : L.k_chunk_bytes);
-      __builtin_amdgcn_global_load_lds(GLB_PTR(src), LDS_PTR(dst + t * 4 * NW * kRowBytes), 16, 0, 0);
+      copy16_per_lane(src, dst + t * 4 * NW * kRowBytes);
     }
   }
 }

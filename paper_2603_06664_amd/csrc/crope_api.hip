@@ -227,5 +227,87 @@ int chunk_attention_limited(const void* q, crope_strides q_strides, int32_t n_q,
                         segs, n_segs, scale, q_limit, true, out, out_strides, lse_or_null, nullptr, 0, stream);
 }
 
+size_t crope_qkv_project_workspace_bytes(int32_t n_tokens, int32_t n_heads, int32_t norm_group) {
+  if (n_tokens <= 0 || n_heads <= 0) return 0;
+  return crope::project_workspace_bytes(n_tokens, n_heads, norm_group == crope::kHeadDim);
+}
+
+int crope_qkv_project_norm_rotate_append(
+    const crope_table_desc* desc, const float* d_table, const void* x, int64_t x_token_stride,
+    const void* w_qkv, const float* bias_or_null, int32_t c_in, const float* gain_q,
+    const float* gain_k, float eps, int32_t norm_group, int32_t n_tokens, int32_t n_heads,
+    int32_t grid_h, int32_t grid_w, int32_t start_frame, int32_t token_offset, void* q_out,
+    crope_strides q_out_strides, void* k_cache, void* v_cache, crope_strides cache_strides,
+    int64_t cache_capacity_tokens, int64_t dst_token, void* workspace, size_t workspace_bytes,
+    void* stream) {
+  if (int rc = check_desc(desc)) return rc;
+  if (!d_table || !x || !w_qkv || !gain_q || !gain_k || !q_out || !k_cache || !v_cache)
+    return fail(CROPE_EINVAL, "null pointer argument");
+  if (n_tokens < 0) return fail(CROPE_EINVAL, "n_tokens is negative");
+  if (n_tokens > 4 * 65535) return fail(CROPE_ERANGE, "more than 262140 tokens in one call");
+  if (n_heads <= 0) return fail(CROPE_EINVAL, "n_heads must be positive");
+  if (n_heads > crope::rope_max_heads())
+    return fail(CROPE_ESHAPE, "n_heads %d exceeds the supported maximum %d", n_heads,
+                crope::rope_max_heads());
+  if (c_in <= 0 || c_in % 64 != 0)
+    return fail(CROPE_ESHAPE, "c_in must be a positive multiple of 64, got %d", c_in);
+  if (c_in > (1 << 20)) return fail(CROPE_ERANGE, "c_in above 2^20");
+  if (grid_h <= 0 || grid_w <= 0) return fail(CROPE_EINVAL, "grid sizes must be positive");
+  if (start_frame < 0 || token_offset < 0)
+    return fail(CROPE_EINVAL, "start_frame and token_offset must be non-negative");
+  if (!(eps >= 0.0f)) return fail(CROPE_EINVAL, "eps must be non-negative");
+  const int64_t hd = (int64_t)n_heads * crope::kHeadDim;
+  if (norm_group != hd && norm_group != crope::kHeadDim)
+    return fail(CROPE_EINVAL, "norm_group must be n_heads*128 (%lld) or 128, got %d",
+                (long long)hd, norm_group);
+  if (!aligned16(d_table) || !aligned16(x) || !aligned16(w_qkv) || !aligned16(gain_q) ||
+      !aligned16(gain_k) || !aligned16(q_out) || !aligned16(k_cache) || !aligned16(v_cache) ||
+      (bias_or_null && !aligned16(bias_or_null)) || (workspace && !aligned16(workspace)))
+    return fail(CROPE_EALIGN, "every base pointer must be 16-byte aligned");
+  if (!stride_ok(x_token_stride) || !stride_ok(q_out_strides.token) || !stride_ok(q_out_strides.head) ||
+      !stride_ok(cache_strides.token) || !stride_ok(cache_strides.head))
+    return fail(CROPE_EALIGN, "strides must be positive multiples of 8 elements");
+  if (x_token_stride < c_in) return fail(CROPE_EINVAL, "x_token_stride smaller than c_in");
+  if (x_token_stride > (1 << 24)) return fail(CROPE_ERANGE, "x_token_stride above 2^24 elements");
+  if (q_out_strides.head < crope::kHeadDim || cache_strides.head < crope::kHeadDim)
+    return fail(CROPE_EINVAL, "head stride smaller than head_dim");
+  if (grid_h > desc->max_h || grid_w > desc->max_w)
+    return fail(CROPE_ERANGE, "grid %dx%d exceeds table extents %dx%d", grid_h, grid_w,
+                desc->max_h, desc->max_w);
+  if (cache_capacity_tokens <= 0) return fail(CROPE_EINVAL, "cache capacity must be positive");
+  if (dst_token < 0 || dst_token + n_tokens > cache_capacity_tokens)
+    return fail(CROPE_ERANGE, "cache rows [%lld, %lld) exceed capacity %lld", (long long)dst_token,
+                (long long)(dst_token + n_tokens), (long long)cache_capacity_tokens);
+  if (n_tokens == 0) { g_err[0] = 0; return CROPE_OK; }
+  const int64_t hw = (int64_t)grid_h * grid_w;
+  const int64_t last_frame = start_frame + ((int64_t)token_offset + n_tokens - 1) / hw;
+  if (last_frame >= desc->max_t)
+    return fail(CROPE_ERANGE, "global frame %lld reaches beyond the time table (max_t %d)",
+                (long long)last_frame, desc->max_t);
+  const bool per_head = norm_group == crope::kHeadDim;
+  const size_t need = crope::project_workspace_bytes(n_tokens, n_heads, per_head);
+  if (need > 0 && (!workspace || workspace_bytes < need))
+    return fail(CROPE_EWORKSPACE, "workspace has %zu bytes, needs %zu", workspace ? workspace_bytes : 0,
+                need);
+
+  crope::ProjArgs a;
+  a.table = d_table; a.tl = crope::table_layout(*desc);
+  a.x = (const uint16_t*)x; a.x_tok = x_token_stride;
+  a.w = (const uint16_t*)w_qkv; a.c_in = c_in; a.bias = bias_or_null;
+  a.gain_q = gain_q; a.gain_k = gain_k; a.eps = eps;
+  a.per_head_norm = per_head ? 1 : 0;
+  a.n_tokens = n_tokens; a.n_heads = n_heads; a.grid_h = grid_h; a.grid_w = grid_w;
+  a.start_frame = start_frame; a.token_offset = token_offset;
+  a.q_out = (uint16_t*)q_out; a.qo_tok = q_out_strides.token; a.qo_head = q_out_strides.head;
+  a.k_cache = (uint16_t*)k_cache; a.v_cache = (uint16_t*)v_cache;
+  a.c_tok = cache_strides.token; a.c_head = cache_strides.head;
+  a.dst_token = dst_token;
+  a.sumsq = (float*)workspace;
+  hipError_t e = crope::launch_project(a, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "crope_qkv_project_norm_rotate_append launch");
+  g_err[0] = 0;
+  return CROPE_OK;
+}
+
 }  // extern "C"
 #pragma GCC visibility pop

@@ -60,10 +60,26 @@ struct AttnArgs {
   void* workspace; size_t workspace_bytes;
 };
 
+struct ProjArgs {
+  const float* table; TableLayout tl;
+  const uint16_t* x; int64_t x_tok;   // [n_tokens][c_in], token stride in elements
+  const uint16_t* w; int c_in;        // [3*H*128][c_in], rows contiguous
+  const float* bias;                  // [3*H*128] or null
+  const float *gain_q, *gain_k;
+  float eps; int per_head_norm;
+  int n_tokens, n_heads, grid_h, grid_w, start_frame, token_offset;
+  uint16_t* q_out; int64_t qo_tok, qo_head;
+  uint16_t *k_cache, *v_cache; int64_t c_tok, c_head;
+  int64_t dst_token;
+  float* sumsq;                       // [2][n_tokens][H] (row-wide norm only)
+};
+
 hipError_t launch_build_table(const crope_table_desc& d, float* table, hipStream_t st);
 hipError_t launch_rope(const RopeArgs& a, hipStream_t st);
 int rope_max_heads();
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
 size_t attention_workspace_bytes(int n_q, int n_heads, int64_t n_keys);
+hipError_t launch_project(const ProjArgs& a, hipStream_t st);
+size_t project_workspace_bytes(int n_tokens, int n_heads, bool per_head_norm);
 
 }  // namespace crope

@@ -148,3 +148,52 @@ def hip_chain(cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, want_lse=
     return dict(q_rot=bits_to_f64(dev_bits(q_out)), k_cache=bits_to_f64(dev_bits(k_cache)),
                 v_cache_bits=dev_bits(v_cache), o=bits_to_f64(dev_bits(out)),
                 lse=lse.cpu().numpy().astype(np.float64) if want_lse else None, segs=segs)
+
+
+# ------------------------------------------------------------------ fused projection
+def oracle_projected(cfg: W.ChunkConfig, pin: W.ProjectionInputs, inp: W.ChunkInputs, norm_group=None,
+                     use_bias=True):
+    """fp64 chain of Algorithm 3 steps 1-3 for the current call's rows: (q~, k~, v)."""
+    import oracle
+    H, D = cfg.n_heads, cfg.head_dim
+    group = H * D if norm_group is None else norm_group
+    return oracle.qkv_project_norm_rotate(
+        bits_to_f64(pin.x), bits_to_f64(pin.w), pin.bias if use_bias else None, inp.gain_q, inp.gain_k,
+        cfg.eps, group, H, cfg.dims, cfg.theta, cfg.grid_h, cfg.grid_w, cfg.start_frame, cfg.token_offset)
+
+
+def hip_projected(cfg: W.ChunkConfig, pin: W.ProjectionInputs, inp: W.ChunkInputs, norm_group=None,
+                  use_bias=True, cap_extra=5, dst=3, x_pad=0):
+    """Runs crope_qkv_project_norm_rotate_append once.  Returns q~ [n,H,D] (fp64 from bf16),
+    the written k rows, the written v rows, and the untouched remainder of the caches (bits)."""
+    import torch
+    import paper_2603_06664_amd as P
+    H, D = cfg.n_heads, cfg.head_dim
+    group = H * D if norm_group is None else norm_group
+    n, c_in = pin.x.shape
+    desc, tab = make_table(P.TableDesc(dim_t=cfg.dims[0], dim_h=cfg.dims[1], dim_w=cfg.dims[2],
+                                       theta=cfg.theta))
+    cap = n + cap_extra
+    canary = 0x7FC1   # a NaN pattern no kernel writes
+    k_cache = torch.full((cap, H, D), 0, dtype=torch.int16, device="cuda").fill_(canary).view(torch.bfloat16)
+    v_cache = k_cache.clone()
+    xs = to_dev_bf16(pin.x)
+    if x_pad:
+        buf = torch.zeros((n, c_in + x_pad), dtype=torch.bfloat16, device="cuda")
+        buf[:, :c_in] = xs
+        xs = buf[:, :c_in]
+    w = to_dev_bf16(pin.w)
+    bias = torch.from_numpy(pin.bias).cuda() if use_bias else None
+    gq = torch.from_numpy(inp.gain_q).cuda()
+    gk = torch.from_numpy(inp.gain_k).cuda()
+    q_out = torch.empty((n, H, D), dtype=torch.bfloat16, device="cuda")
+    ws_bytes = P.crope_qkv_project_workspace_bytes(n, H, group)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    P.crope_qkv_project_norm_rotate_append(desc, tab, xs, w, bias, c_in, gq, gk, cfg.eps, group, n, H,
+                                           cfg.grid_h, cfg.grid_w, cfg.start_frame, cfg.token_offset,
+                                           q_out, k_cache, v_cache, cap, dst, ws, ws_bytes)
+    torch.cuda.synchronize()
+    kb, vb = dev_bits(k_cache), dev_bits(v_cache)
+    untouched = np.concatenate([kb[:dst].ravel(), kb[dst + n:].ravel(), vb[:dst].ravel(), vb[dst + n:].ravel()])
+    return dict(q=bits_to_f64(dev_bits(q_out)), k=bits_to_f64(kb[dst:dst + n]), v=bits_to_f64(vb[dst:dst + n]),
+                untouched_ok=bool(np.all(untouched == canary)))
