@@ -7,7 +7,8 @@
 // fragments as they lie in memory.  The product is formed transposed, C^T = W . x^T
 // (channels = MFMA rows, tokens = columns): an accumulator lane then holds 4 consecutive
 // channels of ONE token, i.e. two whole rotation pairs, and the epilogue needs no cross-lane
-// traffic for the rotation and writes 8-byte pieces of a token row.
+// traffic for the rotation; the bf16 tile is then transposed through LDS and leaves in whole
+// 256-byte (token, head) rows.
 //
 // A work-group (8 waves, 2 x 4) owns 128 output channels (one head of q, k or v) x 256
 // tokens; a wave owns 64 x 64 (four 32x32 accumulators).  The reduction runs in steps of
@@ -51,11 +52,16 @@ constexpr int kStepK = 64;      // reduction elements per LDS stage
 constexpr int kRowB = kStepK * 2;             // 128 B per LDS row
 constexpr int kStageA = kTileCh * kRowB;      // 16 KB
 constexpr int kStageB = kTileTok * kRowB;     // 32 KB
+constexpr int kOutRowB = kTileCh * 2 + 16;    // bf16 output tile row in LDS, padded against bank conflicts
+constexpr int kOutBytes = kTileTok * kOutRowB; // 69632
+constexpr int kAngRowB = 64 * 8 + 16;          // one token's 64 (cos, sin) pairs in LDS, padded (16-byte rows)
+constexpr int kAngBytes = kTileTok * kAngRowB; // 135168
 constexpr int kXcds = 8;
 constexpr int kTokGroup = 4;    // token tiles walked together with 8 channel tiles by one XCD's CUs
 
 struct ProjTiles {
   int ch_tiles, tok_tiles, total, per_xcd;
+  int wgs_per_xcd;   // work-groups launched per XCD (at most its 32 CUs)
 };
 
 struct TileLoader {   // scalars only
@@ -82,15 +88,28 @@ __device__ __forceinline__ void copy16(const uint8_t* base /* wave-uniform */, u
                :: "v"(lane_off), "s"(base), "s"(m0) : "memory");
 }
 
-__device__ __forceinline__ void load_stage(const TileLoader& L, int kt, uint8_t* a_st, uint8_t* b_st) {
+// PART 0, 1, 2: the W tile, the first and the second half of the x tile (two copies each); a
+// step issues the three parts between its MFMA groups instead of all at once, so that the
+// waves do not queue up behind the address unit right after the barrier.
+template <int PART>
+__device__ __forceinline__ void load_stage_part(const TileLoader& L, int kt, uint8_t* a_st, uint8_t* b_st) {
   const uint8_t* ap = L.a_base + (int64_t)kt * kRowB;
   const uint8_t* bp = L.b_base + (int64_t)kt * kRowB;
-  copy16(ap, L.a_off0, a_st + L.lds_off);
-  copy16(ap, L.a_off1, a_st + L.lds_off + 8192);
-  copy16(bp, L.b_off0, b_st + L.lds_off);
-  copy16(bp, L.b_off1, b_st + L.lds_off + 8192);
-  copy16(bp, L.b_off2, b_st + L.lds_off + 16384);
-  copy16(bp, L.b_off3, b_st + L.lds_off + 24576);
+  if (PART == 0) {
+    copy16(ap, L.a_off0, a_st + L.lds_off);
+    copy16(ap, L.a_off1, a_st + L.lds_off + 8192);
+  } else if (PART == 1) {
+    copy16(bp, L.b_off0, b_st + L.lds_off);
+    copy16(bp, L.b_off1, b_st + L.lds_off + 8192);
+  } else {
+    copy16(bp, L.b_off2, b_st + L.lds_off + 16384);
+    copy16(bp, L.b_off3, b_st + L.lds_off + 24576);
+  }
+}
+__device__ __forceinline__ void load_stage(const TileLoader& L, int kt, uint8_t* a_st, uint8_t* b_st) {
+  load_stage_part<0>(L, kt, a_st, b_st);
+  load_stage_part<1>(L, kt, a_st, b_st);
+  load_stage_part<2>(L, kt, a_st, b_st);
 }
 
 struct Frags {
@@ -138,13 +157,16 @@ __device__ __forceinline__ void step(f32x16_t (&acc)[2][2], Frags& f0, Frags& f1
                                      int n_kt, const uint8_t* a_rd, const uint8_t* b_rd, uint8_t* a_ld,
                                      uint8_t* b_ld, const uint8_t* a_nx, const uint8_t* b_nx, int a_off0,
                                      int b_off0) {
-  if (STEADY || kt + 2 < n_kt) load_stage(L, kt + 2, a_ld, b_ld);
+  const bool prefetch = STEADY || kt + 2 < n_kt;
   read_frags(f1, a_rd, b_rd, a_off0, b_off0, 1);
   mfma4(acc, f0);
+  if (prefetch) load_stage_part<0>(L, kt + 2, a_ld, b_ld);
   read_frags(f0, a_rd, b_rd, a_off0, b_off0, 2);
   mfma4(acc, f1);
+  if (prefetch) load_stage_part<1>(L, kt + 2, a_ld, b_ld);
   read_frags(f1, a_rd, b_rd, a_off0, b_off0, 3);
   mfma4(acc, f0);
+  if (prefetch) load_stage_part<2>(L, kt + 2, a_ld, b_ld);
 #pragma unroll
   for (int i = 0; i < 3; ++i) {
     __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // DS reads one sub-step ahead
@@ -178,14 +200,14 @@ __device__ __forceinline__ void unit_to_tile(const ProjTiles& pt, int unit, int&
 template <bool PER_HEAD>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
 void qkv_project_kernel(ProjArgs a, ProjTiles pt) {
-  // separate objects per stage: fragment reads of one stage provably do not alias the
-  // in-flight copies into another
-  __shared__ __attribute__((aligned(1024))) uint8_t a_lds0[kStageA];
-  __shared__ __attribute__((aligned(1024))) uint8_t a_lds1[kStageA];
-  __shared__ __attribute__((aligned(1024))) uint8_t a_lds2[kStageA];
-  __shared__ __attribute__((aligned(1024))) uint8_t b_lds0[kStageB];
-  __shared__ __attribute__((aligned(1024))) uint8_t b_lds1[kStageB];
-  __shared__ __attribute__((aligned(1024))) uint8_t b_lds2[kStageB];
+  // three stages of (W tile 16 KB, x tile 32 KB); the epilogue reuses the space
+  __shared__ __attribute__((aligned(1024))) uint8_t lds[3 * (kStageA + kStageB)];
+  uint8_t* const a_lds0 = lds;
+  uint8_t* const b_lds0 = lds + kStageA;
+  uint8_t* const a_lds1 = lds + (kStageA + kStageB);
+  uint8_t* const b_lds1 = a_lds1 + kStageA;
+  uint8_t* const a_lds2 = lds + 2 * (kStageA + kStageB);
+  uint8_t* const b_lds2 = a_lds2 + kStageA;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -193,8 +215,12 @@ void qkv_project_kernel(ProjArgs a, ProjTiles pt) {
   const int n = lane & 31, g = lane >> 5;
   const int wc = wave & 1, wt = wave >> 1;   // channel half, token quarter of the tile
 
-  const int unit = (int)(blockIdx.x % kXcds) * pt.per_xcd + (int)(blockIdx.x / kXcds);
-  if (unit >= pt.total) return;   // whole work-group leaves before any barrier
+  // Persistent work-groups, one per CU: a work-group walks its XCD's run of the unit list in
+  // strides of the XCD's CU count.  Not ending between tiles lets a tile's output stores drain
+  // under the next tile's reduction instead of holding up the hand-over of the CU.
+  for (int idx = (int)(blockIdx.x / kXcds); idx < pt.per_xcd; idx += pt.wgs_per_xcd) {
+  const int unit = (int)(blockIdx.x % kXcds) * pt.per_xcd + idx;
+  if (unit >= pt.total) break;   // wave-uniform; the whole work-group leaves together
   int ch_tile, tok_tile;
   unit_to_tile(pt, unit, ch_tile, tok_tile);
   const int tok0 = tok_tile * kTileTok;
@@ -258,128 +284,175 @@ void qkv_project_kernel(ProjArgs a, ProjTiles pt) {
   }
 
   // ------------------------------------------------------------------ epilogue
-  // acc[c][t][i]: token tok0 + 64*wt + 32*t + n, channel 64*wc + 32*c + 8*(i/4) + 4*g + i%4 of the head
+  // acc[c][t][i]: token tok0 + 64*wt + 32*t + n, channel 64*wc + 32*c + 8*(i/4) + 4*g + i%4 of the head.
+  // The closing barrier of the last step has passed: every wave is done with the stages.  The
+  // LDS now holds, in turn, the (cos, sin) rows of the tile's 256 tokens (gathered with pairs
+  // on the lane axis, where a token's position is wave-uniform and its 64 pairs are three
+  // contiguous runs of the tables, then read back with tokens on the lane axis at constant
+  // offsets), the sums of squares, and the bf16 output tile, which leaves in whole 256-byte
+  // (token, head) rows.
+  uint8_t* const out_lds = lds;                                     // [256][kOutRowB]
+  uint8_t* const ang_lds = lds;                                     // [256][kAngRowB]: 64 x (cos, sin)
+  float* const ss_lds = reinterpret_cast<float*>(lds + kAngBytes);  // [wc][wt][t][32]
   const int which = ch_tile / a.n_heads;   // 0: q, 1: k, 2: v
   const int head = ch_tile - which * a.n_heads;
-  if (a.bias) {
-    const float* bp = a.bias + (int64_t)ch_tile * kTileCh + 64 * wc + 4 * g;
+  // bias and gain of the lane's 32 channels: all loads issued together, ahead of their use
+  float4 gv[2][4];
+  if (which != 2) {
+    const float* gp = (which == 0 ? a.gain_q : a.gain_k) + head * kHeadDim + 64 * wc + 4 * g;
 #pragma unroll
     for (int c = 0; c < 2; ++c)
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const float4 bv = *reinterpret_cast<const float4*>(bp + 32 * c + 8 * b);
+      for (int b = 0; b < 4; ++b) gv[c][b] = *reinterpret_cast<const float4*>(gp + 32 * c + 8 * b);
+  }
+  if (a.bias) {
+    const float* bp = a.bias + (int64_t)ch_tile * kTileCh + 64 * wc + 4 * g;
+    float4 bv[2][4];
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) bv[c][b] = *reinterpret_cast<const float4*>(bp + 32 * c + 8 * b);
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          acc[c][t][4 * b + 0] += bv.x; acc[c][t][4 * b + 1] += bv.y;
-          acc[c][t][4 * b + 2] += bv.z; acc[c][t][4 * b + 3] += bv.w;
+          acc[c][t][4 * b + 0] += bv[c][b].x; acc[c][t][4 * b + 1] += bv[c][b].y;
+          acc[c][t][4 * b + 2] += bv[c][b].z; acc[c][t][4 * b + 3] += bv[c][b].w;
         }
-      }
   }
-  int tok[2];
-  tok[0] = tok0 + 64 * wt + n;
-  tok[1] = tok[0] + 32;
+  uint32_t packed[2][2][4][2];   // [t][c][b][pair of the 4 channels]
 
-  if (which == 2) {   // v: one rounding, straight into the cache
+  if (which == 2) {   // v: one rounding
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      if (tok[t] >= a.n_tokens) continue;
-      uint16_t* dst = a.v_cache + (a.dst_token + tok[t]) * a.c_tok + (int64_t)head * a.c_head + 64 * wc + 4 * g;
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-          uint2 o;
-          o.x = pack_bf16x2(acc[c][t][4 * b + 0], acc[c][t][4 * b + 1]);
-          o.y = pack_bf16x2(acc[c][t][4 * b + 2], acc[c][t][4 * b + 3]);
-          *reinterpret_cast<uint2*>(dst + 32 * c + 8 * b) = o;
+          packed[t][c][b][0] = pack_bf16x2(acc[c][t][4 * b + 0], acc[c][t][4 * b + 1]);
+          packed[t][c][b][1] = pack_bf16x2(acc[c][t][4 * b + 2], acc[c][t][4 * b + 3]);
         }
+  } else {
+    const int p_t = a.tl.pairs_t, p_h = a.tl.pairs_h, p_w = a.tl.pairs_w, p_th = p_t + p_h;
+    const float2* tab2 = reinterpret_cast<const float2*>(a.table);
+    // ---- gather: wave w fetches the rows of tile tokens 32w .. 32w+31.  Positions are decoded
+    // with tokens on the lane axis; for the fetch the lane axis is the pair index (a token's
+    // 64 pairs are three contiguous runs of the tables) and token rr's table row offsets are
+    // broadcast from lane rr.  Lane j needs exactly one of the three offsets.
+    {
+      const int last_tok = a.n_tokens - 1;
+      const int ig = a.token_offset + min(tok0 + 32 * wave + n, last_tok);   // past the end: last token's position
+      const int hw = a.grid_h * a.grid_w;
+      const int pf = ig / hw;
+      const int rem = ig - pf * hw;
+      const int ph = rem / a.grid_w;
+      const int pw = rem - ph * a.grid_w;
+      const int row_t = (a.start_frame + pf) * p_t, row_h = ph * p_h, row_w = pw * p_w;
+      const int j = lane;
+      const bool is_t = j < p_t, is_h = !is_t && j < p_th;
+      const int m_t = is_t ? -1 : 0, m_h = is_h ? -1 : 0, m_w = (is_t || is_h) ? 0 : -1;
+      const int cb = is_t ? (int)(a.tl.off_t / 2) + j
+                          : is_h ? (int)(a.tl.off_h / 2) + (j - p_t) : (int)(a.tl.off_w / 2) + (j - p_th);
+      uint8_t* dst = ang_lds + (32 * wave) * kAngRowB + lane * 8;
+      float2 row[32];
+#pragma unroll
+      for (int rr = 0; rr < 32; ++rr) {
+        const int st = __builtin_amdgcn_readlane(row_t, rr), sh = __builtin_amdgcn_readlane(row_h, rr),
+                  sw = __builtin_amdgcn_readlane(row_w, rr);
+        row[rr] = tab2[cb + ((st & m_t) | (sh & m_h) | (sw & m_w))];
+      }
+#pragma unroll
+      for (int rr = 0; rr < 32; ++rr) *reinterpret_cast<float2*>(dst + rr * kAngRowB) = row[rr];
     }
-    return;
+    // ---- sums of squares over the head: lane-local, the other half of the wave, the other wave
+    float tot[2];
+    {
+      float ss[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        float sq = 0.f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sq = fmaf(acc[c][t][i], acc[c][t][i], sq);
+        ss[t] = sum_across_halves(sq);
+      }
+      if (g == 0) {
+        ss_lds[((wc * 4 + wt) * 2 + 0) * 32 + n] = ss[0];
+        ss_lds[((wc * 4 + wt) * 2 + 1) * 32 + n] = ss[1];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+        tot[t] = ss_lds[((0 * 4 + wt) * 2 + t) * 32 + n] + ss_lds[((1 * 4 + wt) * 2 + t) * 32 + n];
+    }
+    float r[2];
+    if (PER_HEAD) {
+      r[0] = 1.0f / sqrtf(tot[0] * (1.0f / kHeadDim) + a.eps);
+      r[1] = 1.0f / sqrtf(tot[1] * (1.0f / kHeadDim) + a.eps);
+    } else {
+      r[0] = r[1] = 1.0f;
+      if (wc == 0 && g == 0) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const int token = tok0 + 64 * wt + 32 * t + n;
+          if (token < a.n_tokens) a.sumsq[((int64_t)which * a.n_tokens + token) * a.n_heads + head] = tot[t];
+        }
+      }
+    }
+    // ---- normalise, gain, rotate; the lane's pairs are 32*wc + 2*g + (16*c + 4*b + e)
+    const uint8_t* ang_lane = ang_lds + (64 * wt + n) * kAngRowB + (32 * wc + 2 * g) * 8;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const float4 cs = *reinterpret_cast<const float4*>(ang_lane + 32 * t * kAngRowB + (16 * c + 4 * b) * 8);
+          const float xa0 = acc[c][t][4 * b + 0] * r[t] * gv[c][b].x, xb0 = acc[c][t][4 * b + 1] * r[t] * gv[c][b].y;
+          const float xa1 = acc[c][t][4 * b + 2] * r[t] * gv[c][b].z, xb1 = acc[c][t][4 * b + 3] * r[t] * gv[c][b].w;
+          packed[t][c][b][0] = pack_bf16x2(xa0 * cs.x - xb0 * cs.y, xa0 * cs.y + xb0 * cs.x);
+          packed[t][c][b][1] = pack_bf16x2(xa1 * cs.z - xb1 * cs.w, xa1 * cs.w + xb1 * cs.z);
+        }
+      }
+    __syncthreads();   // every wave has read its angles: the output tile may overwrite them
   }
 
-  // sums of squares over the head: lane-local, the other half of the wave, the other wave
-  float tot[2];
+  // ---- the tile leaves in whole token rows: 16 lanes x 16 B = the 256 bytes of one (token, head)
   {
-    float ss[2];
+    uint8_t* out_lane = out_lds + (64 * wt + n) * kOutRowB + (64 * wc + 4 * g) * 2;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      float s = 0.f;
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s = fmaf(acc[c][t][i], acc[c][t][i], s);
-      ss[t] = sum_across_halves(s);
-    }
-    // (the barrier that closed the last step: every wave is done with the LDS stages)
-    float* ss_lds = reinterpret_cast<float*>(a_lds0);   // [wc][wt][t][32]
-    if (g == 0) {
-      ss_lds[((wc * 4 + wt) * 2 + 0) * 32 + n] = ss[0];
-      ss_lds[((wc * 4 + wt) * 2 + 1) * 32 + n] = ss[1];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-      tot[t] = ss_lds[((0 * 4 + wt) * 2 + t) * 32 + n] + ss_lds[((1 * 4 + wt) * 2 + t) * 32 + n];
+        for (int b = 0; b < 4; ++b)
+          *reinterpret_cast<uint2*>(out_lane + 32 * t * kOutRowB + (32 * c + 8 * b) * 2) =
+              make_uint2(packed[t][c][b][0], packed[t][c][b][1]);
   }
-  float r[2];
-  if (PER_HEAD) {
-    r[0] = 1.0f / sqrtf(tot[0] * (1.0f / kHeadDim) + a.eps);
-    r[1] = 1.0f / sqrtf(tot[1] * (1.0f / kHeadDim) + a.eps);
-  } else {
-    r[0] = r[1] = 1.0f;
-    if (wc == 0 && g == 0) {
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-        if (tok[t] < a.n_tokens) a.sumsq[((int64_t)which * a.n_tokens + tok[t]) * a.n_heads + head] = tot[t];
-    }
-  }
-
-  // table rows of the lane's two tokens (index decode with the global time index)
-  const float2* tab2 = reinterpret_cast<const float2*>(a.table);
-  int bt[2], bh[2], bw[2];
+  __syncthreads();
   {
-    const int hw = a.grid_h * a.grid_w;
+    uint16_t* base;
+    int64_t tstride;
+    if (which == 0) { base = a.q_out + (int64_t)head * a.qo_head; tstride = a.qo_tok; }
+    else {
+      base = (which == 1 ? a.k_cache : a.v_cache) + a.dst_token * a.c_tok + (int64_t)head * a.c_head;
+      tstride = a.c_tok;
+    }
+    const int chunk = tid & 15;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int ig = a.token_offset + min(tok[t], a.n_tokens - 1);
-      const int f = ig / hw;
-      const int rem = ig - f * hw;
-      const int ph = rem / a.grid_w;
-      const int pw = rem - ph * a.grid_w;
-      const int ptime = a.start_frame + f;
-      bt[t] = (int)(a.tl.off_t / 2) + ptime * a.tl.pairs_t;
-      bh[t] = (int)(a.tl.off_h / 2) + ph * a.tl.pairs_h - a.tl.pairs_t;
-      bw[t] = (int)(a.tl.off_w / 2) + pw * a.tl.pairs_w - a.tl.pairs_t - a.tl.pairs_h;
+    for (int it = 0; it < 8; ++it) {
+      const int row = (tid >> 4) + 32 * it;
+      const int token = tok0 + row;
+      if (token < a.n_tokens)
+        *reinterpret_cast<uint4*>(base + (int64_t)token * tstride + chunk * 8) =
+            *reinterpret_cast<const uint4*>(out_lds + row * kOutRowB + chunk * 16);
     }
   }
-  const float* gain = (which == 0 ? a.gain_q : a.gain_k) + head * kHeadDim + 64 * wc + 4 * g;
-  uint16_t* dst[2];
-#pragma unroll
-  for (int t = 0; t < 2; ++t)
-    dst[t] = (which == 0 ? a.q_out + (int64_t)tok[t] * a.qo_tok + (int64_t)head * a.qo_head
-                         : a.k_cache + (a.dst_token + tok[t]) * a.c_tok + (int64_t)head * a.c_head) +
-             64 * wc + 4 * g;
-  const int p_t = a.tl.pairs_t, p_th = a.tl.pairs_t + a.tl.pairs_h;
-#pragma unroll
-  for (int c = 0; c < 2; ++c)
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const float4 gv = *reinterpret_cast<const float4*>(gain + 32 * c + 8 * b);
-      const int j0 = 32 * wc + 16 * c + 4 * b + 2 * g;   // pair index of channels 4*b .. +1
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        if (tok[t] >= a.n_tokens) continue;
-        const int i0 = j0 + (j0 < p_t ? bt[t] : j0 < p_th ? bh[t] : bw[t]);
-        const int i1 = j0 + 1 + (j0 + 1 < p_t ? bt[t] : j0 + 1 < p_th ? bh[t] : bw[t]);
-        const float2 cs0 = tab2[i0], cs1 = tab2[i1];
-        const float xa0 = acc[c][t][4 * b + 0] * r[t] * gv.x, xb0 = acc[c][t][4 * b + 1] * r[t] * gv.y;
-        const float xa1 = acc[c][t][4 * b + 2] * r[t] * gv.z, xb1 = acc[c][t][4 * b + 3] * r[t] * gv.w;
-        uint2 o;
-        o.x = pack_bf16x2(xa0 * cs0.x - xb0 * cs0.y, xa0 * cs0.y + xb0 * cs0.x);
-        o.y = pack_bf16x2(xa1 * cs1.x - xb1 * cs1.y, xa1 * cs1.y + xb1 * cs1.x);
-        *reinterpret_cast<uint2*>(dst[t] + 32 * c + 8 * b) = o;
-      }
-    }
+  __syncthreads();   // the output tile has been read: the next tile's copies may overwrite it
+  }   // next unit
 }
 
 // Second pass of the row-wide norm: one wave per (tensor, token) sums the per-head sums of
@@ -421,7 +494,8 @@ hipError_t launch_project(const ProjArgs& a, hipStream_t st) {
   pt.tok_tiles = (a.n_tokens + kTileTok - 1) / kTileTok;
   pt.total = pt.ch_tiles * pt.tok_tiles;
   pt.per_xcd = (pt.total + kXcds - 1) / kXcds;
-  const dim3 grid(pt.per_xcd * kXcds), block(512);
+  pt.wgs_per_xcd = pt.per_xcd < 32 ? pt.per_xcd : 32;
+  const dim3 grid(pt.wgs_per_xcd * kXcds), block(512);
   if (a.per_head_norm) hipLaunchKernelGGL(qkv_project_kernel<true>, grid, block, 0, st, a, pt);
   else hipLaunchKernelGGL(qkv_project_kernel<false>, grid, block, 0, st, a, pt);
   hipError_t e = hipGetLastError();
