@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C4", choices=["C1", "C2", "C3", "C4", "C5", "R288", "R960", "C5P", "C4R"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-projection", action="store_true",
+                    help="skip the separate timing of the fused QKV projection entry point")
     ap.add_argument("--cpu-rows", type=int, default=1024,
                     help="query rows of the workload the CPU oracle is timed on")
     ap.add_argument("--input-sets", type=int, default=8,
@@ -176,6 +178,58 @@ def main():
                           "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get("crope_qk_norm_rotate_append"),
                           "algorithmic_bytes_per_launch": rope_bytes},
     }
+
+    # Beside the step: the local QKV projection fused with norm + RoPE + cache update (the
+    # next row of the path, Algorithm 3 step 1 folded in), timed on its own at the same token
+    # count with model width c_in = H*128, against the same work done as a vendor GEMM followed
+    # by crope_qk_norm_rotate_append.  Both norm readings; inputs rotate over 4 sets.
+    if not args.no_projection:
+        c_in = H * D
+        pin = W.make_projection_inputs(cfg)
+        w_qkv = Hn.to_dev_bf16(pin.w)
+        bias = torch.from_numpy(pin.bias).cuda()
+        xs = [Hn.to_dev_bf16(pin.x)]
+        for _ in range(3):
+            xs.append(xs[0].clone())
+        proj_flops = 2.0 * n * c_in * 3 * H * D
+        y_buf = torch.empty((n, 3 * H * D), dtype=torch.bfloat16, device="cuda")
+        bias_bf16 = bias.to(torch.bfloat16)
+        fused = {}
+        for label, grp in (("norm_per_head", D), ("norm_row_wide", H * D)):
+            pws_bytes = P.crope_qkv_project_workspace_bytes(n, H, grp)
+            pws = torch.empty(max(pws_bytes, 16), dtype=torch.uint8, device="cuda")
+
+            def fused_call(i, grp=grp, pws=pws, pws_bytes=pws_bytes):
+                P.crope_qkv_project_norm_rotate_append(desc, tab, xs[i % 4], w_qkv, bias, c_in, gq, gk,
+                                                       cfg.eps, grp, n, H, cfg.grid_h, cfg.grid_w, s, off,
+                                                       q_rot, k_cache, v_cache, cap, dst, pws, pws_bytes)
+
+            def unfused_call(i, grp=grp):
+                torch.addmm(bias_bf16, xs[i % 4], w_qkv.t(), out=y_buf)
+                y = y_buf.view(n, 3, H, D)
+                P.crope_qk_norm_rotate_append(desc, tab, y[:, 0], y[:, 1], y[:, 2], gq, gk, cfg.eps, grp,
+                                              n, H, cfg.grid_h, cfg.grid_w, s, off, q_rot, k_cache,
+                                              v_cache, cap, dst)
+
+            for i in range(20):
+                fused_call(i)
+                unfused_call(i)
+            t_f = min(timed(fused_call) for _ in range(3))
+            t_u = min(timed(unfused_call) for _ in range(3))
+            fused[label] = {"ms": round(t_f, 5), "tflops": round(proj_flops / (t_f * 1e-3) / 1e12, 1),
+                            "vendor_gemm_then_append_ms": round(t_u, 5)}
+        best = fused["norm_per_head"]
+        result["fused_projection"] = {
+            "kernel": "crope_qkv_project_norm_rotate_append", "c_in": c_in, "tokens": n,
+            "algorithmic_flops_per_launch": proj_flops, **fused,
+            "roofline": {"bound": "mfma", "achieved": best["tflops"], "peak": PEAK_BF16_TFLOPS,
+                         "unit": "TFLOP/s", "frac": round(best["tflops"] / PEAK_BF16_TFLOPS, 4),
+                         "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name, {}).get(
+                             "crope_qkv_project_norm_rotate_append")}}
+        # the timed calls above overwrote the chunk's cache rows and q_rot with projected data:
+        # restore the step's own result for the parity sample
+        step(0)
+        torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
         import oracle
