@@ -58,6 +58,19 @@ def main():
                                       v_cache, cap, dst_row)
         P.chunk_attention(q_rot, n, H, k_cache, v_cache, cap, [(0, nk)], D ** -0.5, out, None, ws,
                           ws_bytes)
+    # the fused projection entry point (both norm readings), model width c_in = H*128
+    c_in = H * D
+    xs = [torch.randn(n, c_in, device=dev, dtype=torch.bfloat16) for _ in range(4)]
+    w_qkv = (torch.randn(3 * H * D, c_in, device=dev) * c_in ** -0.5).to(torch.bfloat16)
+    bias = 0.1 * torch.randn(3 * H * D, device=dev)
+    pws_bytes = P.crope_qkv_project_workspace_bytes(n, H, H * D)
+    pws = torch.empty(max(pws_bytes, 16), dtype=torch.uint8, device=dev)
+    for i in range(args.iters):
+        grp = D if i % 2 == 0 else H * D
+        P.crope_qkv_project_norm_rotate_append(desc, tab, xs[i % 4], w_qkv, bias, c_in, gq, gk, cfg.eps, grp,
+                                               n, H, cfg.grid_h, cfg.grid_w, cfg.start_frame,
+                                               cfg.token_offset, q_rot, k_cache, v_cache, cap, dst_row, pws,
+                                               pws_bytes)
     torch.cuda.synchronize()
     print("profile_run done: %s, %d iterations, copy %d bytes" % (cfg.name, args.iters, COPY_BYTES))
 
