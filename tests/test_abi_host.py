@@ -142,3 +142,49 @@ def test_build_table_rejects_small_buffer():
     with pytest.raises(P.CropeError) as ei:
         P.crope_build_table(d, _FakeTensor(A + 4, (1 << 20,), esize=4))
     assert ei.value.code == B.CROPE_EALIGN
+
+
+class _FakeMatrix(_FakeTensor):
+    def is_contiguous(self): return True
+
+
+def _project(n=24, H=2, c_in=256, x_addr=A, w_addr=A, x_stride=None, cap=72, dst=48, group=256, ws=A,
+             ws_bytes=1 << 20, desc=None, gh=4, gw=6, s=5):
+    desc = desc or P.TableDesc()
+    x = _FakeMatrix(x_addr, (n, c_in), [c_in if x_stride is None else x_stride, 1])
+    w = _FakeMatrix(w_addr, (3 * H * 128, c_in))
+    out = _FakeTensor(A, (max(n, 1), H, 128))
+    c = _FakeTensor(A, (cap, H, 128))
+    tab = _FakeTensor(A, (1,), esize=4)
+    g = _FakeTensor(A, (H * 128,), esize=4)
+    wsp = None if ws is None else _FakeTensor(ws, (ws_bytes,), esize=1)
+    P.crope_qkv_project_norm_rotate_append(desc, tab, x, w, None, c_in, g, g, 1e-6, group, n, H, gh, gw, s, 0,
+                                           out, c, c, cap, dst, wsp, ws_bytes if ws is not None else 0)
+
+
+@pytest.mark.parametrize("kwargs,code", [
+    (dict(c_in=96), B.CROPE_ESHAPE),                 # not a multiple of 64
+    (dict(c_in=0), B.CROPE_ESHAPE),
+    (dict(x_addr=A + 8), B.CROPE_EALIGN),
+    (dict(w_addr=0), B.CROPE_EINVAL),
+    (dict(x_stride=128), B.CROPE_EINVAL),            # row stride smaller than c_in
+    (dict(x_stride=260), B.CROPE_EALIGN),            # rows not 16-byte aligned
+    (dict(dst=49), B.CROPE_ERANGE),
+    (dict(group=64), B.CROPE_EINVAL),
+    (dict(ws=None), B.CROPE_EWORKSPACE),             # the row-wide norm needs its scratch
+    (dict(ws_bytes=16), B.CROPE_EWORKSPACE),
+    (dict(desc=P.TableDesc(max_t=5)), B.CROPE_ERANGE),
+    (dict(n=-1), B.CROPE_EINVAL),
+])
+def test_project_rejects_bad_arguments(kwargs, code):
+    with pytest.raises(P.CropeError) as ei:
+        _project(**kwargs)
+    assert ei.value.code == code
+    assert ei.value.message
+
+
+def test_project_zero_tokens_is_a_noop_and_workspace_sizes():
+    _project(n=0, dst=72)
+    assert P.crope_qkv_project_workspace_bytes(4680, 12, 128) == 0
+    assert P.crope_qkv_project_workspace_bytes(4680, 12, 1536) == 2 * 4680 * 12 * 4
+    assert P.crope_qkv_project_workspace_bytes(0, 12, 1536) == 0
