@@ -25,8 +25,8 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # by what the same counter reads for a 1 GiB copy (x2.000 and x1.000); the summary with the
 # commands is profiles/chunk_attention_and_rope_C4_pmc.md.  Other workloads report null.
 MEASURED_TRAFFIC_BYTES = {
-    "C4": {"chunk_attention": (162802.0 * 2.000 + 14041.7 * 1.000) * 1024,
-           "crope_qk_norm_rotate_append": (21203.2 * 2.000 + 42120.0 * 1.000) * 1024,
+    "C4": {"chunk_attention": (162809.3 * 2.000 + 14046.1 * 1.000) * 1024,
+           "crope_qk_norm_rotate_append": (21204.7 * 2.000 + 42120.0 * 1.000) * 1024,
            # profiles/qkv_project_C4_kernel_trace_and_pmc.md (per-head norm variant)
            "crope_qkv_project_norm_rotate_append": (76935.5 * 2.000 + 42120.0 * 1.000) * 1024},
 }
