@@ -155,3 +155,33 @@ def test_errors(P):
     assert e.value.code == -4
     P.crope_qkv_project_norm_rotate_append(*args(c_in, ws, 0))   # and the valid call goes through
     torch.cuda.synchronize()
+
+
+def test_strided_outputs(P):
+    """q_out and the caches as views into wider buffers (token and head strides larger than the
+    dense ones): results equal the dense call bit for bit and nothing else is written."""
+    import torch
+    cfg, c_in = SMALL[2]
+    H, D, n = cfg.n_heads, cfg.head_dim, cfg.n_q
+    inp = W.make_inputs(cfg)
+    pin = W.make_projection_inputs(cfg, c_in=c_in)
+    dense = Hn.hip_projected(cfg, pin, inp, dst=0, cap_extra=0)
+    desc, tab = Hn.make_table(P.TableDesc())
+    x, w = Hn.to_dev_bf16(pin.x), Hn.to_dev_bf16(pin.w)
+    bias = torch.from_numpy(pin.bias).cuda()
+    gq, gk = torch.from_numpy(inp.gain_q).cuda(), torch.from_numpy(inp.gain_k).cuda()
+    canary = 0x7FC1
+    def wide():
+        return torch.zeros((n, H + 1, D + 64), dtype=torch.int16, device="cuda").fill_(canary).view(torch.bfloat16)
+    qb, kb, vb = wide(), wide(), wide()
+    q_out, kc, vc = qb[:, :H, :D], kb[:, :H, :D], vb[:, :H, :D]
+    ws_bytes = P.crope_qkv_project_workspace_bytes(n, H, H * D)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    P.crope_qkv_project_norm_rotate_append(desc, tab, x, w, bias, c_in, gq, gk, cfg.eps, H * D, n, H, cfg.grid_h,
+                                           cfg.grid_w, cfg.start_frame, cfg.token_offset, q_out, kc, vc, n, 0,
+                                           ws, ws_bytes)
+    torch.cuda.synchronize()
+    for name, buf in (("q", qb), ("k", kb), ("v", vb)):
+        bits = Hn.dev_bits(buf)
+        np.testing.assert_array_equal(Hn.bits_to_f64(bits[:, :H, :D]), dense[name])
+        assert np.all(bits[:, H:, :] == canary) and np.all(bits[:, :, D:] == canary), name
