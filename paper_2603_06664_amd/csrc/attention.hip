@@ -312,19 +312,25 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   // the same K/V rows at the same time share one L2.
   const int unit = (int)(blockIdx.x % kXcds) * sp.units_per_xcd + (int)(blockIdx.x / kXcds);
   if (unit >= sp.total_units) return;   // whole work-group leaves before any barrier
-  const int q_tile = unit % sp.q_tiles;
+  // under per-query limits later query tiles usually see more keys: start the long ones first
+  const int q_tile = LIMITED ? sp.q_tiles - 1 - unit % sp.q_tiles : unit % sp.q_tiles;
   const int hs = unit / sp.q_tiles;
   const int split = hs % sp.n_splits;
   const int head = hs / sp.n_splits;
   const int q0 = q_tile * BM + wave * 32;
   int n_keys = (int)a.n_keys;
   int lim = n_keys;   // keys visible to this lane's query
+  int n_unmasked = 0;  // LIMITED: key tiles wholly below the smallest limit of this wave's queries
   if (LIMITED) {
     const int qrow = min(q0 + n, a.n_q - 1);
     lim = min(n_keys, max(1, a.q_limit[qrow]));
-    int wmax = lim;
+    int wmax = lim, wmin = lim;
 #pragma unroll
-    for (int m = 16; m >= 1; m >>= 1) wmax = max(wmax, __shfl_xor(wmax, m, 64));
+    for (int m = 16; m >= 1; m >>= 1) {
+      wmax = max(wmax, __shfl_xor(wmax, m, 64));
+      wmin = min(wmin, __shfl_xor(wmin, m, 64));
+    }
+    n_unmasked = __builtin_amdgcn_readfirstlane(wmin) / BN;
     // largest limit of the work-group, through the (still unused) first K buffer
     int* scratch = reinterpret_cast<int*>(k_lds0);
     if (lane == 0) scratch[wave] = wmax;
@@ -419,6 +425,12 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
 
   // ---- steady state: iteration T scores tile T+1 (K) and accumulates tile T (V)
   int T = 0;
+  if (LIMITED) {   // tiles below every limit of this wave: the unmasked code (same barriers per iteration)
+    for (; T + 3 < n_t && T + 2 < n_unmasked; T += 2) {
+      tile_iteration<NW, false>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);
+      tile_iteration<NW, false>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, lim, g, c, tau);
+    }
+  }
   for (; T + 3 < n_t; T += 2) {
     tile_iteration<NW, LIMITED>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);       // even T
     tile_iteration<NW, LIMITED>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, lim, g, c, tau);   // odd T

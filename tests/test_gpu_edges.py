@@ -187,14 +187,16 @@ def _limited_case(P, n_q, H, n_k, limits, seed):
     return Hn.bits_to_f64(Hn.dev_bits(out)), o_ref, lse.cpu().numpy().astype(np.float64), lse_ref
 
 
-@pytest.mark.parametrize("kind", ["block_causal", "token_causal", "ragged", "clamped"])
+@pytest.mark.parametrize("kind", ["block_causal", "token_causal", "ragged", "clamped", "block_causal_long"])
 def test_attention_with_per_query_limits(P, kind):
     """One pass over a whole sequence with the generator's block-causal rule (and other prefix
     masks) against the oracle's masked attention."""
     print("case", kind, flush=True)
-    n = 600
+    n = 1500 if kind == "block_causal_long" else 600
     i = np.arange(n)
-    if kind == "block_causal":
+    if kind == "block_causal_long":
+        limits = (i // 333 + 1) * 333          # block ends inside key tiles; many unmasked tiles below them
+    elif kind == "block_causal":
         limits = (i // 150 + 1) * 150          # blocks of 150 tokens: query sees up to the end of its block
     elif kind == "token_causal":
         limits = i + 1
