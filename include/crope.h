@@ -181,8 +181,8 @@ size_t crope_qkv_project_workspace_bytes(int32_t n_tokens, int32_t n_heads, int3
  *   workspace      device, >= crope_qkv_project_workspace_bytes(...) bytes, 16-byte aligned; may
  *                  be NULL when that size is 0.  Contents are undefined afterwards.
  * Everything else, and every error, as for crope_qk_norm_rotate_append; additionally
- * CROPE_ESHAPE if c_in is not a positive multiple of 64, CROPE_ERANGE if x_token_stride
- * exceeds 2^24, CROPE_EWORKSPACE if the workspace is missing or too small.  x and w_qkv must
+ * CROPE_ESHAPE if c_in is not a positive multiple of 64, CROPE_ERANGE if c_in exceeds 2^20 or
+ * x_token_stride exceeds 2^24, CROPE_EWORKSPACE if the workspace is missing or too small.  x and w_qkv must
  * not overlap any output. */
 int crope_qkv_project_norm_rotate_append(
     const crope_table_desc* desc, const float* d_table,
