@@ -266,6 +266,7 @@ def main():
                       "oracle norm+rotate of all visible keys and the chunk's queries: %.2f s"
                       % (rows, cfg.n_q, n_keys, t_att, t_rot),
             "attention_seconds_full_extrapolated": round(t_att * cfg.n_q / rows, 1),
+            "gpu_over_oracle": round(attn_tflops / (cpu_flops / t_att / 1e12), 0),
         }
         got = Hn.bits_to_f64(Hn.dev_bits(out))[ridx]
         mx, rl, _ = Hn.errors(got, o_ref)
