@@ -35,7 +35,7 @@ def _random_config(seed: int) -> W.ChunkConfig:
                          k_head_scale=bool(rng.random() < 0.3), **kwargs)
 
 
-@pytest.mark.parametrize("seed", range(14))
+@pytest.mark.parametrize("seed", range(32))
 def test_random_chunk(seed):
     cfg = _random_config(seed)
     print("random chunk %d: H=%d grid %dx%d frames %d..%d chunk %d q=%d keys=%d ring=%s off=%d"
@@ -55,7 +55,7 @@ def test_random_chunk(seed):
     assert np.max(np.abs(got["lse"] - ref["lse"])) <= 2e-2
 
 
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(20))
 def test_random_projection(seed):
     cfg = _random_config(100 + seed)
     rng = np.random.default_rng(5000 + seed)
@@ -74,3 +74,37 @@ def test_random_projection(seed):
     Hn.assert_close("k", got["k"], k, strict_abs=per_head and not cfg.k_head_scale)
     Hn.assert_close("v", got["v"], v, strict_abs=True)
     assert got["untouched_ok"]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_limited_attention(seed):
+    """Random per-query prefix limits (sorted, blocky or arbitrary) against the oracle's mask."""
+    import torch
+    import oracle
+    import paper_2603_06664_amd as P
+    rng = np.random.default_rng(9000 + seed)
+    H = int(rng.choice([1, 2, 5, 12]))
+    n_q = int(rng.integers(1, 700))
+    n_k = int(rng.integers(1, 1500))
+    kind = seed % 3
+    if kind == 0:
+        limits = np.sort(rng.integers(1, n_k + 1, size=n_q))
+    elif kind == 1:
+        blk = int(rng.integers(1, max(2, n_k // 3)))
+        limits = np.minimum(n_k, (np.arange(n_q) * n_k // max(n_q, 1) // blk + 1) * blk)
+    else:
+        limits = rng.integers(1, n_k + 1, size=n_q)
+    print("random limited %d: H=%d n_q=%d n_k=%d kind=%d" % (seed, H, n_q, n_k, kind), flush=True)
+    qb = W.f32_to_bf16_bits(rng.standard_normal((n_q, H, 128), dtype=np.float32))
+    kb = W.f32_to_bf16_bits(rng.standard_normal((n_k, H, 128), dtype=np.float32))
+    vb = W.f32_to_bf16_bits(rng.standard_normal((n_k, H, 128), dtype=np.float32))
+    q, k, v = Hn.to_dev_bf16(qb), Hn.to_dev_bf16(kb), Hn.to_dev_bf16(vb)
+    out = torch.empty_like(q)
+    lse = torch.empty((H, n_q), dtype=torch.float32, device="cuda")
+    lim = torch.from_numpy(limits.astype(np.int32)).cuda()
+    P.chunk_attention_limited(q, n_q, H, k, v, n_k, [(0, n_k)], Hn.SCALE, lim, out, lse)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.attention(Hn.bits_to_f64(qb), Hn.bits_to_f64(kb), Hn.bits_to_f64(vb), Hn.SCALE,
+                                      q_block=(limits - 1).astype(np.int32), k_block=np.arange(n_k, dtype=np.int32))
+    Hn.assert_close("o", Hn.bits_to_f64(Hn.dev_bits(out)), o_ref)
+    assert np.max(np.abs(lse.cpu().numpy().astype(np.float64) - lse_ref)) <= 2e-2
