@@ -95,7 +95,8 @@ int crope_build_table(const crope_table_desc* desc, float* d_table, size_t bytes
  *                   or 128 (per head)
  *   grid_h, grid_w  latent token grid of one frame; must be <= max_h, max_w
  *   start_frame     s, global index of the chunk's first frame
- *   token_offset    Delta = rank * (chunk tokens / ranks); 0 on one GPU
+ *   token_offset    Delta = rank * (chunk tokens / ranks); 0 on one GPU;
+ *                   token_offset + n_tokens must stay below 2^31 (CROPE_ERANGE)
  *   q_out           device bf16 [n_tokens][n_heads][128], strides q_out_strides
  *   k_cache,v_cache device bf16 [cache_capacity_tokens][n_heads][128], strides cache_strides
  * Errors: CROPE_ERANGE if any row's t_global >= max_t or dst_token + n_tokens exceeds the

@@ -88,6 +88,8 @@ int crope_qk_norm_rotate_append(
   if (grid_h <= 0 || grid_w <= 0) return fail(CROPE_EINVAL, "grid sizes must be positive");
   if (start_frame < 0 || token_offset < 0)
     return fail(CROPE_EINVAL, "start_frame and token_offset must be non-negative");
+  if ((int64_t)token_offset + n_tokens > INT32_MAX)
+    return fail(CROPE_ERANGE, "token_offset + n_tokens exceeds 2^31-1");
   if (!(eps >= 0.0f)) return fail(CROPE_EINVAL, "eps must be non-negative");
   const int64_t hd = (int64_t)n_heads * crope::kHeadDim;
   if (norm_group != hd && norm_group != crope::kHeadDim)
@@ -255,6 +257,8 @@ int crope_qkv_project_norm_rotate_append(
   if (grid_h <= 0 || grid_w <= 0) return fail(CROPE_EINVAL, "grid sizes must be positive");
   if (start_frame < 0 || token_offset < 0)
     return fail(CROPE_EINVAL, "start_frame and token_offset must be non-negative");
+  if ((int64_t)token_offset + n_tokens > INT32_MAX)
+    return fail(CROPE_ERANGE, "token_offset + n_tokens exceeds 2^31-1");
   if (!(eps >= 0.0f)) return fail(CROPE_EINVAL, "eps must be non-negative");
   const int64_t hd = (int64_t)n_heads * crope::kHeadDim;
   if (norm_group != hd && norm_group != crope::kHeadDim)

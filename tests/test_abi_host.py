@@ -89,6 +89,8 @@ def _append(desc=None, q_addr=A, n=24, H=2, gh=4, gw=6, s=5, off=0, cap=72, dst=
     (dict(s=-1), B.CROPE_EINVAL),
     (dict(tab_addr=0), B.CROPE_EINVAL),
     (dict(off=24, desc=P.TableDesc(max_t=6)), B.CROPE_ERANGE),  # offset pushes rows into frame 6
+    (dict(off=2**31 - 10, desc=P.TableDesc(max_t=1 << 20, max_h=1 << 10, max_w=1 << 11), gh=1 << 10,
+          gw=1 << 11, s=0), B.CROPE_ERANGE),                    # 32-bit token index would wrap
 ])
 def test_append_rejects_bad_arguments(kwargs, code):
     with pytest.raises(P.CropeError) as ei:
