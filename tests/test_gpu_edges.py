@@ -107,7 +107,7 @@ def test_attention_increasing_scores(P):
     Hn.assert_close("o", Hn.bits_to_f64(Hn.dev_bits(out)), o_ref)
 
 
-@pytest.mark.parametrize("H", [1, 7, 33, 64])
+@pytest.mark.parametrize("H", [1, 7, 16, 24, 33, 64])
 def test_rope_head_counts(P, H):
     print("case heads", H, flush=True)
     cfg = W.ChunkConfig("RH%d" % H, 50 + H, H, 3, 5, start_frame=2, n_frames=2, first_kv_frame=2)
@@ -119,6 +119,24 @@ def test_rope_head_counts(P, H):
         Hn.assert_close("k_cache", got["k_cache"], ref["k_cache"])
         assert np.array_equal(got["v_cache_bits"], inp.v)
         Hn.assert_close("o", got["o"], ref["o"])
+
+
+@pytest.mark.parametrize("H", [16, 21, 40, 64])
+def test_rope_many_tokens_of_many_heads(P, H):
+    """More than 2048 tokens of 16..64 heads: one wave walks a whole row in up to 16 rounds
+    (below that token count such head counts take the four-waves-per-row kernel)."""
+    print("case heads", H, "tokens 2100", flush=True)
+    cfg = W.ChunkConfig("RM%d" % H, 80 + H, H, 30, 35, start_frame=1, n_frames=2, first_kv_frame=1)
+    assert cfg.n_q == 2100
+    inp = W.make_inputs(cfg)
+    rows = [0, 1049, 1050, 2099]
+    for group in (H * 128, 128):
+        ref = Hn.oracle_chain(cfg, inp, norm_group=group, q_rows=rows)
+        got = Hn.hip_chain(cfg, inp, norm_group=group)
+        Hn.assert_close("q_rot", got["q_rot"], ref["q_rot"])
+        Hn.assert_close("k_cache", got["k_cache"], ref["k_cache"])
+        assert np.array_equal(got["v_cache_bits"], inp.v)
+        Hn.assert_close("o", got["o"][rows], ref["o"])
 
 
 def test_rope_far_time_positions(P):
