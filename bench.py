@@ -15,9 +15,8 @@ import sys
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-for p in (ROOT, os.path.join(ROOT, "tests")):
-    if p not in sys.path:
-        sys.path.insert(0, p)
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
@@ -41,12 +40,84 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-projection", action="store_true",
                     help="skip the separate timing of the fused QKV projection entry point")
-    ap.add_argument("--cpu-rows", type=int, default=1024,
-                    help="query rows of the workload the CPU oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=0,
+                    help="query rows of the workload the CPU oracle is timed on (0 = all of them)")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the MFMA-only loop and the plain copy that measure this GPU's own ceilings")
     ap.add_argument("--input-sets", type=int, default=8,
                     help="disjoint q/k/v input sets rotated between steps so the append kernel "
                          "reads from HBM, not from the 256 MB last-level cache")
     return ap.parse_args()
+
+
+def _ceilings_lib():
+    import ctypes
+    from paper_2603_06664_amd import build
+    lib = ctypes.CDLL(build.CEILINGS_LIB)
+    lib.ceiling_mfma_operand_bytes.restype = ctypes.c_size_t
+    lib.ceiling_mfma_flops.restype = ctypes.c_double
+    lib.ceiling_mfma_flops.argtypes = [ctypes.c_int]
+    lib.ceiling_mfma_launch.restype = ctypes.c_int
+    lib.ceiling_mfma_launch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    lib.ceiling_copy_launch.restype = ctypes.c_int
+    lib.ceiling_copy_launch.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    return lib
+
+
+def _events_ms(torch, fn, reps):
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(reps):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def measure_mfma_ceiling(torch, attn_tflops):
+    """What the matrix pipes of THIS GPU sustain with nothing else going on: 8 waves per CU
+    issuing only bf16 MFMAs on random operands for about the duration of one attention launch."""
+    lib = _ceilings_lib()
+    st = torch.cuda.current_stream().cuda_stream
+    ops = torch.randn(lib.ceiling_mfma_operand_bytes() // 2, device="cuda").to(torch.bfloat16)
+    sink = torch.zeros(512 * 256, dtype=torch.float32, device="cuda")
+    iters = 6000   # ~0.9 ms per launch at 1.6 PFLOP/s
+
+    def run(i):
+        rc = lib.ceiling_mfma_launch(ops.data_ptr(), sink.data_ptr(), iters, st)
+        assert rc == 0, "ceiling_mfma_launch: hipError %d" % rc
+    for i in range(5):
+        run(i)
+    ms = min(_events_ms(torch, run, 20) for _ in range(3))
+    tf = lib.ceiling_mfma_flops(iters) / (ms * 1e-3) / 1e12
+    return {"ceiling_mfma": {"what": "MFMA-only loop (v_mfma_f32_32x32x16_bf16, random bf16 operands in "
+                                     "registers, 8 waves on each of the 256 CUs), measured in this run",
+                             "tflops": round(tf, 1), "frac_of_datasheet_peak": round(tf / PEAK_BF16_TFLOPS, 4)},
+            "frac_of_ceiling_mfma": round(attn_tflops / tf, 4)}
+
+
+def measure_copy_ceiling(torch, sb, rope_bytes, rope_gbps, steps):
+    """A plain 16-byte-per-lane copy that moves as many bytes as the append kernel (half read,
+    half written), sources rotating over as many disjoint buffers as the append's inputs."""
+    lib = _ceilings_lib()
+    st = torch.cuda.current_stream().cuda_stream
+    half = (int(rope_bytes) // 2 + 15) // 16 * 16
+    srcs = [torch.empty(half, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(len(sb.sets))]
+    dstb = torch.empty(half, dtype=torch.uint8, device="cuda")
+
+    def run(i):
+        rc = lib.ceiling_copy_launch(dstb.data_ptr(), srcs[i % len(srcs)].data_ptr(), half, st)
+        assert rc == 0, "ceiling_copy_launch: hipError %d" % rc
+    for i in range(10):
+        run(i)
+    ms = min(_events_ms(torch, run, steps) for _ in range(3))
+    gbps = 2.0 * half / (ms * 1e-3) / 1e9
+    return {"ceiling_copy": {"what": "plain device copy, 16 B per lane, %d bytes read + %d written per launch, "
+                                     "sources rotating over %d buffers, measured in this run" % (half, half, len(srcs)),
+                             "gbps": round(gbps, 1), "us": round(ms * 1e3, 2),
+                             "frac_of_datasheet_peak": round(gbps / PEAK_HBM_GBPS, 4)},
+            "frac_of_ceiling_copy": round(rope_gbps / gbps, 4)}
 
 
 def main():
@@ -58,61 +129,30 @@ def main():
     import numpy as np
     import torch
     import paper_2603_06664_amd as P
-    from paper_2603_06664_amd import binding, workloads as W
+    from paper_2603_06664_amd import binding, devutil, workloads as W
     binding._load()   # no fallback: raises if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    import harness as Hn
 
     cfg = W.CONFIGS[args.workload]
     H, D = cfg.n_heads, cfg.head_dim
     inp = W.make_inputs(cfg)
-    desc, tab = Hn.make_table()
-    cap = cfg.capacity_frames * cfg.hw
-    k_cache = torch.zeros((cap, H, D), dtype=torch.bfloat16, device="cuda")
-    v_cache = torch.zeros_like(k_cache)
-    k_all, v_all = Hn.to_dev_bf16(inp.k), Hn.to_dev_bf16(inp.v)
-    gq, gk = torch.from_numpy(inp.gain_q).cuda(), torch.from_numpy(inp.gain_k).cuda()
-    group = H * D
+    # tables, gains, the cache filled the way generation would have (untimed), and
+    # args.input_sets copies of the call's inputs at different addresses
+    sb = devutil.StepBuffers(cfg, inp, input_sets=args.input_sets)
+    desc, tab, gq, gk, group = sb.desc, sb.tab, sb.gq, sb.gk, sb.group
+    k_cache, v_cache, cap = sb.k_cache, sb.v_cache, sb.cap
+    s, n, off, dst = sb.s, sb.n, sb.off, sb.dst
+    sets, q_rot, out, lse = sb.sets, sb.q_rot, sb.out, sb.lse
+    segs, n_keys, ws, ws_bytes = sb.segs, sb.n_keys, sb.ws, sb.ws_bytes
+    SETUP_STEPS = 15
 
-    # fill the cache the way generation would (history blocks and other shards), untimed
-    cur = None
-    scratch = torch.empty((cfg.chunk_tokens, H, D), dtype=torch.bfloat16, device="cuda")
-    for (s, nf, row0, n, off, is_cur) in W.chunk_schedule(cfg):
-        if is_cur:
-            cur = (s, row0, n, off)
-        P.crope_qk_norm_rotate_append(desc, tab, k_all[row0:row0 + n], k_all[row0:row0 + n],
-                                      v_all[row0:row0 + n], gq, gk, cfg.eps, group, n, H, cfg.grid_h,
-                                      cfg.grid_w, s, off, scratch[:n], k_cache, v_cache, cap,
-                                      Hn.dst_row(cfg, s, off))
-    s, row0, n, off = cur
-    dst = Hn.dst_row(cfg, s, off)
-    # rotating input sets for the timed append (set 0 = the real inputs; others are copies
-    # at different addresses so every step streams from HBM)
-    q0 = Hn.to_dev_bf16(inp.q)
-    sets = [(q0, k_all[row0:row0 + n], v_all[row0:row0 + n])]
-    for _ in range(max(0, args.input_sets - 1)):
-        sets.append(tuple(t.clone() for t in sets[0]))
-    q_rot = torch.empty_like(q0)
-    out = torch.empty_like(q0)
-    lse = torch.empty((H, cfg.n_q), dtype=torch.float32, device="cuda")
-    segs = Hn.visible_segments(cfg)
-    n_keys = sum(m for _, m in segs)
-    ws_bytes = P.chunk_attention_workspace_bytes(cfg.n_q, H, n_keys)
-    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
-
-    def step(i, ev=None):
-        q, k, v = sets[i % len(sets)]
-        if ev: ev[0].record()
-        P.crope_qk_norm_rotate_append(desc, tab, q, k, v, gq, gk, cfg.eps, group, n, H, cfg.grid_h,
-                                      cfg.grid_w, s, off, q_rot, k_cache, v_cache, cap, dst)
-        if ev: ev[1].record()
-        P.chunk_attention(q_rot, cfg.n_q, H, k_cache, v_cache, cap, segs, Hn.SCALE, out, lse, ws,
-                          ws_bytes)
-        if ev: ev[2].record()
+    def step(i):
+        sb.append(i)
+        sb.attention()
 
     # setup: the first launches upload the code objects and ramp the clocks; not part of the
     # W warm-up steps the caller asked for
-    for i in range(15):
+    for i in range(SETUP_STEPS):
         step(i)
     torch.cuda.synchronize()
     for i in range(args.warmup):
@@ -140,13 +180,10 @@ def main():
         return e0.elapsed_time(e1) / args.steps
 
     def rope_only(i):
-        q, k, v = sets[i % len(sets)]
-        P.crope_qk_norm_rotate_append(desc, tab, q, k, v, gq, gk, cfg.eps, group, n, H, cfg.grid_h,
-                                      cfg.grid_w, s, off, q_rot, k_cache, v_cache, cap, dst)
+        sb.append(i)
 
     def attn_only(i):
-        P.chunk_attention(q_rot, cfg.n_q, H, k_cache, v_cache, cap, segs, Hn.SCALE, out, lse, ws,
-                          ws_bytes)
+        sb.attention()
 
     rope_runs = [timed(rope_only) for _ in range(3)]
     attn_runs = [timed(attn_only) for _ in range(3)]
@@ -164,7 +201,7 @@ def main():
     result = {
         "metric": "chunk attention TFLOP/s + fused RoPE GB/s; ms per 480P chunk (1 GPU)",
         "value": round(value, 3), "unit": "TFLOP/s (attention FLOPs / whole-step time)",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "setup_launches_before_warmup": SETUP_STEPS,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "%s: %d heads, %d queries x %d keys, d=128, grid %dx%d, start_frame %d"
@@ -193,9 +230,9 @@ def main():
     if not args.no_projection:
         c_in = H * D
         pin = W.make_projection_inputs(cfg)
-        w_qkv = Hn.to_dev_bf16(pin.w)
+        w_qkv = devutil.to_dev_bf16(pin.w)
         bias = torch.from_numpy(pin.bias).cuda()
-        xs = [Hn.to_dev_bf16(pin.x)]
+        xs = [devutil.to_dev_bf16(pin.x)]
         for _ in range(3):
             xs.append(xs[0].clone())
         proj_flops = 2.0 * n * c_in * 3 * H * D
@@ -238,39 +275,51 @@ def main():
         step(0)
         torch.cuda.synchronize()
 
+    if not args.no_ceilings:
+        result["roofline"].update(measure_mfma_ceiling(torch, attn_tflops))
+        result["roofline_rope"].update(measure_copy_ceiling(torch, sb, rope_bytes, rope_gbps, args.steps))
+
     if not args.no_cpu_baseline:
         import oracle
-        rows = min(args.cpu_rows, cfg.n_q)
-        ridx = np.linspace(0, cfg.n_q - 1, rows).astype(np.int64)
+        rows = cfg.n_q if args.cpu_rows <= 0 else min(args.cpu_rows, cfg.n_q)
+        ridx = np.arange(cfg.n_q) if rows == cfg.n_q else np.linspace(0, cfg.n_q - 1, rows).astype(np.int64)
+        kf = devutil.bits_to_f64(inp.k)
+        vf = devutil.bits_to_f64(inp.v)
         t0 = time.perf_counter()
-        kf = Hn.bits_to_f64(inp.k)
-        vf = Hn.bits_to_f64(inp.v)
-        t_conv = time.perf_counter() - t0
-        t0 = time.perf_counter()
-        # rotated keys of every visible frame (what the cache holds), then the sampled rows
-        k_rot = np.empty_like(kf)
+        # what the cache holds: rotated keys of every visible frame, written block by block at the
+        # rows the schedule gives them, then gathered in the order of the visible segments
+        cache = oracle.Cache(cap, H, D)
         for (cs, nf, r0, cn, coff, _) in W.chunk_schedule(cfg):
-            k_rot[r0:r0 + cn] = oracle.qk_norm_rotate(kf[r0:r0 + cn], inp.gain_k, cfg.eps, group,
-                                                     cfg.dims, cfg.theta, cfg.grid_h, cfg.grid_w, cs, coff)
-        q_rot_o = oracle.qk_norm_rotate(Hn.bits_to_f64(inp.q), inp.gain_q, cfg.eps, group, cfg.dims,
+            k_rot = oracle.qk_norm_rotate(kf[r0:r0 + cn], inp.gain_k, cfg.eps, group, cfg.dims, cfg.theta,
+                                          cfg.grid_h, cfg.grid_w, cs, coff)
+            cache.write(devutil.dst_row(cfg, cs, coff), k_rot, vf[r0:r0 + cn])
+        kk, vv = cache.gather(segs)
+        q_rot_o = oracle.qk_norm_rotate(devutil.bits_to_f64(inp.q), inp.gain_q, cfg.eps, group, cfg.dims,
                                         cfg.theta, cfg.grid_h, cfg.grid_w, s, off)
         t_rot = time.perf_counter() - t0
         t0 = time.perf_counter()
-        o_ref, _ = oracle.attention(q_rot_o[ridx], k_rot, vf, Hn.SCALE)
+        o_ref, lse_ref = oracle.attention(q_rot_o[ridx], kk, vv, devutil.SCALE)
         t_att = time.perf_counter() - t0
         cpu_flops = 4.0 * rows * n_keys * D * H
         result["cpu_baseline"] = {
             "value": round(cpu_flops / t_att / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.num_threads(),
             "kind": "oracle",
-            "sample": "fp64 oracle attention on %d of %d query rows (all heads, all %d keys): %.2f s; "
+            "sample": "fp64 oracle attention on %s query rows (all heads, all %d keys): %.2f s; "
                       "oracle norm+rotate of all visible keys and the chunk's queries: %.2f s"
-                      % (rows, cfg.n_q, n_keys, t_att, t_rot),
-            "attention_seconds_full_extrapolated": round(t_att * cfg.n_q / rows, 1),
+                      % ("all %d" % rows if rows == cfg.n_q else "%d of %d" % (rows, cfg.n_q), n_keys, t_att, t_rot),
+            "attention_seconds": round(t_att, 2), "rows": rows,
             "gpu_over_oracle": round(attn_tflops / (cpu_flops / t_att / 1e12), 0),
         }
-        got = Hn.bits_to_f64(Hn.dev_bits(out))[ridx]
-        mx, rl, _ = Hn.errors(got, o_ref)
-        result["parity_sample"] = {"rows": rows, "max_abs": float("%.3e" % mx), "rel_l2": float("%.3e" % rl)}
+        # parity of the timed step's own output against the oracle, same rows
+        got = devutil.bits_to_f64(devutil.dev_bits(out))[ridx]
+        diff = np.abs(got - o_ref)
+        lse_got = lse.cpu().numpy().astype(np.float64)[:, ridx]
+        result["parity"] = {"rows": rows, "of": cfg.n_q,
+                            "o_max_abs": float("%.3e" % diff.max()),
+                            "o_rel_l2": float("%.3e" % (np.sqrt((diff ** 2).sum() / (o_ref ** 2).sum()))),
+                            "lse_max_abs": float("%.3e" % np.abs(lse_got - lse_ref).max()),
+                            "within_tolerance": bool(diff.max() <= 2e-2 and
+                                                     np.sqrt((diff ** 2).sum() / (o_ref ** 2).sum()) <= 1e-2)}
     print(json.dumps(result))
 
 

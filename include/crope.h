@@ -2,11 +2,12 @@
  * crope.h — C ABI of the per-chunk attention step of causal autoregressive video-DiT
  * inference with Causal-RoPE, for AMD MI355X (gfx950).
  *
- * The three operations follow the optimized sequence-parallel self-attention call of the
+ * The operations follow the optimized sequence-parallel self-attention call of the
  * paper (Algorithm 3): step 2/3 (global token offset, causal 3D RoPE computed locally
  * from the global start frame), step 5 (KV-cache update) and step 6 (attention of the
- * chunk's queries over the whole cache).  The projection (step 1) and the collectives
- * (steps 4, 7) are outside this library.
+ * chunk's queries over the whole cache).  The local projection (step 1) is available fused
+ * with steps 2, 3 and 5 as crope_qkv_project_norm_rotate_append.  The collectives (steps 4, 7)
+ * are outside this library.
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers to caller-owned memory unless a parameter is
@@ -17,6 +18,8 @@
  *     back to back on one stream execute in order (append, then attention).
  *   - Return value: CROPE_OK (0) or a negative error code.  On error nothing has been
  *     launched and crope_last_error() returns a thread-local, human-readable message.
+ *   - The library keeps no state between calls except that error string: how a call divides
+ *     its work depends on its arguments only.
  *   - Activations are bf16, laid out [token][head][128] with the 128 head channels
  *     contiguous; token and head strides are given in elements.
  */
@@ -93,7 +96,8 @@ int crope_build_table(const crope_table_desc* desc, float* d_table, size_t bytes
  *   eps             RMSNorm epsilon
  *   norm_group      n_heads*128 (statistics over the token's whole projection vector)
  *                   or 128 (per head)
- *   grid_h, grid_w  latent token grid of one frame; must be <= max_h, max_w
+ *   grid_h, grid_w  latent token grid of one frame; must be <= max_h, max_w, and
+ *                   grid_h * grid_w below 2^31 (CROPE_ERANGE)
  *   start_frame     s, global index of the chunk's first frame
  *   token_offset    Delta = rank * (chunk tokens / ranks); 0 on one GPU;
  *                   token_offset + n_tokens must stay below 2^31 (CROPE_ERANGE)
@@ -134,12 +138,48 @@ size_t chunk_attention_workspace_bytes(int32_t n_q, int32_t n_heads, int64_t n_k
  *   workspace      device scratch of >= chunk_attention_workspace_bytes(...) bytes, 16-byte
  *                  aligned; may be NULL when that size is 0.  Contents are undefined after.
  * n_q == 0 is a no-op.  Limits (CROPE_ERANGE beyond): cache capacity < 2^31 rows, cache token
- * stride <= 2^24 elements, at most 2^30 visible keys. */
+ * stride <= 2^24 elements, at most 2^30 visible keys.  Head strides below 128 are CROPE_EINVAL. */
 int chunk_attention(
     const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
     const void* k_cache, const void* v_cache, crope_strides cache_strides,
     int64_t cache_capacity_tokens,
     const crope_kv_segment* segs, int32_t n_segs, float scale,
+    void* out, crope_strides out_strides, float* lse_or_null,
+    void* workspace, size_t workspace_bytes, void* stream);
+
+/* How chunk_attention divides its work (host memory).  A field that is 0 is chosen by the
+ * library from the problem size. */
+typedef struct {
+  int32_t waves;  /* waves per work-group, 32 queries each: 4 or 8                         */
+  int32_t splits; /* 1..16 ranges of the visible keys handled by separate work-groups and
+                     merged by a second kernel; lowered until no range is empty            */
+} crope_attention_plan;
+
+/* Resolve a plan: on entry the non-zero fields of *plan are kept, on return every field holds
+ * the value chunk_attention_planned would use for this problem size (all zeros on entry gives
+ * the plan chunk_attention itself uses).  CROPE_EINVAL for a null pointer, non-positive sizes
+ * or field values outside the ranges above. */
+int chunk_attention_choose_plan(int32_t n_q, int32_t n_heads, int64_t n_keys,
+                                crope_attention_plan* plan);
+
+/* Bytes of scratch chunk_attention_planned needs with `plan` (NULL = automatic); 0 also for
+ * an invalid plan. */
+size_t chunk_attention_planned_workspace_bytes(int32_t n_q, int32_t n_heads, int64_t n_keys,
+                                               const crope_attention_plan* plan);
+
+/* chunk_attention (Algorithm 3 step 6) with the work division given by the caller instead of
+ * chosen by the library; for tuning and for tests that must reach every kernel shape.  The
+ * result differs between plans by rounding only (a split changes the summation order).
+ *   plan       host; NULL or all zeros = exactly chunk_attention
+ *   workspace  >= chunk_attention_planned_workspace_bytes(n_q, n_heads, total keys, plan)
+ * Everything else, and every error, as for chunk_attention; CROPE_EINVAL for a field outside
+ * its range. */
+int chunk_attention_planned(
+    const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
+    const void* k_cache, const void* v_cache, crope_strides cache_strides,
+    int64_t cache_capacity_tokens,
+    const crope_kv_segment* segs, int32_t n_segs, float scale,
+    const crope_attention_plan* plan,
     void* out, crope_strides out_strides, float* lse_or_null,
     void* workspace, size_t workspace_bytes, void* stream);
 
@@ -160,7 +200,8 @@ int chunk_attention_limited(
     const int32_t* q_limit,
     void* out, crope_strides out_strides, float* lse_or_null, void* stream);
 
-/* Bytes of scratch crope_qkv_project_norm_rotate_append needs (0 for norm_group == 128). */
+/* Bytes of scratch crope_qkv_project_norm_rotate_append needs (0 for norm_group == 128; for the
+ * row-wide norm about 512 bytes per token and head). */
 size_t crope_qkv_project_workspace_bytes(int32_t n_tokens, int32_t n_heads, int32_t norm_group);
 
 /* Local QKV projection fused with crope_qk_norm_rotate_append (Algorithm 3 steps 1, 2, 3 and
@@ -171,9 +212,10 @@ size_t crope_qkv_project_workspace_bytes(int32_t n_tokens, int32_t n_heads, int3
  * h*128..h*128+127 of each.  q and k are then normalised, rotated and stored, and v stored,
  * exactly as crope_qk_norm_rotate_append does, but from the fp32 accumulators: y is never
  * rounded to bf16.  With norm_group == 128 every output is rounded once.  With norm_group ==
- * n_heads*128 the 1/rms factor of a token is only known once all heads are done, so q and k
- * are stored as rotate(gain*y) and multiplied by 1/rms in place by a second pass (two
- * roundings; error at most 2^-8 relative).
+ * n_heads*128 the 1/rms factor of a token is only known once all heads are done, so
+ * z = rotate(gain*y) is first stored as two bf16 numbers (bf16(z) in the destination row, the
+ * bf16 of the remainder in the workspace) and a second pass stores the bf16 rounding of their
+ * sum times 1/rms: one rounding of the fp32 value up to 2^-17 relative.
  *
  *   x              device bf16 [n_tokens][c_in], row stride x_token_stride elements
  *   w_qkv          device bf16 [3*n_heads*128][c_in], contiguous ([out][in] like a linear layer)
@@ -183,7 +225,7 @@ size_t crope_qkv_project_workspace_bytes(int32_t n_tokens, int32_t n_heads, int3
  *                  be NULL when that size is 0.  Contents are undefined afterwards.
  * Everything else, and every error, as for crope_qk_norm_rotate_append; additionally
  * CROPE_ESHAPE if c_in is not a positive multiple of 64, CROPE_ERANGE if c_in exceeds 2^20 or
- * x_token_stride exceeds 2^24, CROPE_EWORKSPACE if the workspace is missing or too small.  x and w_qkv must
+ * x_token_stride exceeds 2^22, CROPE_EWORKSPACE if the workspace is missing or too small.  x and w_qkv must
  * not overlap any output. */
 int crope_qkv_project_norm_rotate_append(
     const crope_table_desc* desc, const float* d_table,

@@ -6,7 +6,8 @@ Importing the package does not load the library; the first call does, and fails 
 if it cannot.
 """
 from .binding import (  # noqa: F401
-    CropeError, TableDesc, chunk_attention, chunk_attention_limited, chunk_attention_workspace_bytes, crope_build_table,
+    CropeError, TableDesc, chunk_attention, chunk_attention_choose_plan, chunk_attention_limited,
+    chunk_attention_planned, chunk_attention_planned_workspace_bytes, chunk_attention_workspace_bytes, crope_build_table,
     crope_last_error, crope_qk_norm_rotate_append, crope_qkv_project_norm_rotate_append,
     crope_qkv_project_workspace_bytes, crope_table_bytes, crope_version, library_path,
 )

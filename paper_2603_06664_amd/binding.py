@@ -38,6 +38,10 @@ class _Segment(ctypes.Structure):
     _fields_ = [("start", ctypes.c_int64), ("len", ctypes.c_int64)]
 
 
+class _Plan(ctypes.Structure):
+    _fields_ = [("waves", ctypes.c_int32), ("splits", ctypes.c_int32)]
+
+
 @dataclass(frozen=True)
 class TableDesc:
     """Mirror of crope_table_desc."""
@@ -89,6 +93,14 @@ def _load():
     lib.chunk_attention.argtypes = [
         vp, _Strides, i32, i32, vp, vp, _Strides, i64, ctypes.POINTER(_Segment), i32, f32, vp,
         _Strides, vp, vp, ctypes.c_size_t, vp]
+    lib.chunk_attention_choose_plan.restype = ctypes.c_int
+    lib.chunk_attention_choose_plan.argtypes = [i32, i32, i64, ctypes.POINTER(_Plan)]
+    lib.chunk_attention_planned_workspace_bytes.restype = ctypes.c_size_t
+    lib.chunk_attention_planned_workspace_bytes.argtypes = [i32, i32, i64, ctypes.POINTER(_Plan)]
+    lib.chunk_attention_planned.restype = ctypes.c_int
+    lib.chunk_attention_planned.argtypes = [
+        vp, _Strides, i32, i32, vp, vp, _Strides, i64, ctypes.POINTER(_Segment), i32, f32,
+        ctypes.POINTER(_Plan), vp, _Strides, vp, vp, ctypes.c_size_t, vp]
     lib.chunk_attention_limited.restype = ctypes.c_int
     lib.chunk_attention_limited.argtypes = [
         vp, _Strides, i32, i32, vp, vp, _Strides, i64, ctypes.POINTER(_Segment), i32, f32, vp, vp,
@@ -185,6 +197,41 @@ def chunk_attention(q, n_q: int, n_heads: int, k_cache, v_cache, cache_capacity_
         _ptr(q), _strides(q), n_q, n_heads, _ptr(k_cache), _ptr(v_cache), sc,
         cache_capacity_tokens, arr, len(segs), scale, _ptr(out), _strides(out), _ptr(lse),
         _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def _plan(plan) -> Optional[_Plan]:
+    """plan: None or a (waves, splits) pair; 0 = chosen by the library."""
+    return None if plan is None else _Plan(int(plan[0]), int(plan[1]))
+
+
+def chunk_attention_choose_plan(n_q: int, n_heads: int, n_keys: int, plan=(0, 0)) -> Tuple[int, int]:
+    p = _plan(plan)
+    _check(_load().chunk_attention_choose_plan(n_q, n_heads, n_keys, ctypes.byref(p)))
+    return int(p.waves), int(p.splits)
+
+
+def chunk_attention_planned_workspace_bytes(n_q: int, n_heads: int, n_keys: int, plan=None) -> int:
+    p = _plan(plan)
+    return int(_load().chunk_attention_planned_workspace_bytes(n_q, n_heads, n_keys,
+                                                               None if p is None else ctypes.byref(p)))
+
+
+def chunk_attention_planned(q, n_q: int, n_heads: int, k_cache, v_cache, cache_capacity_tokens: int,
+                            segs: Sequence[Tuple[int, int]], scale: float, plan, out, lse=None,
+                            workspace=None, workspace_bytes: int = 0, stream=None) -> None:
+    sc = _strides(k_cache)
+    if _strides(v_cache).token != sc.token or _strides(v_cache).head != sc.head:
+        raise CropeError(CROPE_EINVAL, "k_cache and v_cache must share strides")
+    arr = (_Segment * max(1, len(segs)))()
+    for i, (s, n) in enumerate(segs):
+        arr[i].start, arr[i].len = int(s), int(n)
+    if workspace is not None and workspace_bytes == 0:
+        workspace_bytes = workspace.numel() * workspace.element_size()
+    p = _plan(plan)
+    _check(_load().chunk_attention_planned(
+        _ptr(q), _strides(q), n_q, n_heads, _ptr(k_cache), _ptr(v_cache), sc,
+        cache_capacity_tokens, arr, len(segs), scale, None if p is None else ctypes.byref(p),
+        _ptr(out), _strides(out), _ptr(lse), _ptr(workspace), workspace_bytes, _stream(stream)))
 
 
 def chunk_attention_limited(q, n_q: int, n_heads: int, k_cache, v_cache, cache_capacity_tokens: int,

@@ -15,7 +15,6 @@
 // wave's does.  K and V tiles of 64 keys are copied HBM -> LDS without passing through
 // registers (global_load_lds, 16 B per lane), double buffered, XOR-swizzled by choosing
 // which global chunk each lane fetches.
-#include <cstdlib>
 #include "crope_internal.h"
 
 namespace crope {
@@ -214,7 +213,9 @@ struct Loader {     // scalars only, so that it is promoted to registers at once
 };
 
 // 16 bytes per lane, HBM -> LDS without passing through registers: lane i's data lands at
-// LDS address lds_dst + 16*i (the LDS base travels in M0).  Written as inline assembly, not
+// LDS address lds_dst + 16*i.  The LDS base travels in M0, which the compiler loads itself
+// (an input operand bound to that register); the s_nop covers the wait state the hardware
+// wants between a write of M0 and a copy that uses it.  Written as inline assembly, not
 // with the compiler's builtin: while a builtin copy is in flight the compiler's wait-count
 // insertion turns every later "wait for this LDS read" into "wait for ALL LDS reads", which
 // exposes the full LDS latency at each MFMA that consumes a fragment.  The copies are
@@ -223,13 +224,13 @@ struct Loader {     // scalars only, so that it is promoted to registers at once
 __device__ __forceinline__ void copy16_uniform(const uint8_t* base /* wave-uniform */, uint32_t lane_off,
                                                uint8_t* lds_dst /* wave-uniform */) {
   const uint32_t m0 = __builtin_amdgcn_readfirstlane(LDS_ADDR(lds_dst));
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(lane_off), "s"(base), "s"(m0) : "memory");
+  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(lane_off), "s"(base), "{m0}"(m0) : "memory");
 }
 __device__ __forceinline__ void copy16_per_lane(const uint8_t* src, uint8_t* lds_dst /* wave-uniform */) {
   const uint32_t m0 = __builtin_amdgcn_readfirstlane(LDS_ADDR(lds_dst));
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(src), "s"(m0) : "memory");
+  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(src), "{m0}"(m0) : "memory");
 }
 
 __device__ __forceinline__ int seg_row(const Loader& L, int vk) {
@@ -245,7 +246,11 @@ __device__ __forceinline__ void load_tile(const Loader& L, int tile, uint8_t* ds
   const int k_last = k_first + BN - 1;
   const uint8_t* head = IS_V ? L.v_head : L.k_head;
   const int r_first = seg_row(L, k_first);
-  if (k_last < L.n_keys && seg_row(L, k_last) - r_first == BN - 1) {
+  // no segment ends inside (k_first, k_last]: both keys lie in one segment, whose rows are consecutive
+  const bool one_segment = !((k_first < L.seg_end0 && k_last >= L.seg_end0) ||
+                             (k_first < L.seg_end1 && k_last >= L.seg_end1) ||
+                             (k_first < L.seg_end2 && k_last >= L.seg_end2));
+  if (k_last < L.n_keys && one_segment) {
     // 64 consecutive cache rows: uniform base + constant per-lane offset
     const uint8_t* base = head + (int64_t)r_first * L.row_bytes;
     const uint32_t lane_off = IS_V ? L.v_lane_off : L.k_lane_off;
@@ -530,32 +535,29 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a, SplitInfo sp) 
 constexpr int kCus = 256;
 constexpr int kMaxSplits = 16;
 
-struct Plan {
-  int waves;    // waves per work-group: 4 (two work-groups per CU) or 8 (one)
-  int splits;   // key splits
-};
-
 // Pick the work-group shape and the number of key splits.  Cost = key tiles on the critical
 // path of the busiest CU slot, in units of one 4-wave work-group tile; an 8-wave work-group
 // shares its K/V copies between twice the queries and runs its tile ~4 % faster (measured).  Every
-// split costs a partial-result round trip, so a split must pay for itself.
-Plan choose_plan(int n_q, int n_heads, int64_t n_keys) {
-  // CROPE_ATTN_SPLITS=<n> pins the number of key splits, CROPE_ATTN_WAVES=<4|8> the
-  // work-group shape (tuning aids); unset or 0 = automatic
-  static const int forced_s = [] { const char* e = getenv("CROPE_ATTN_SPLITS"); return e ? atoi(e) : 0; }();
-  static const int forced_w = [] { const char* e = getenv("CROPE_ATTN_WAVES"); return e ? atoi(e) : 0; }();
+// split costs a partial-result round trip, so a split must pay for itself.  Non-zero fields of
+// `want` pin that choice; a pinned split count is lowered until no split is empty.
+AttnPlan choose_plan(int n_q, int n_heads, int64_t n_keys, AttnPlan want) {
   const int n_tiles = (int)((n_keys + BN - 1) / BN);
-  Plan best{4, 1};
+  if (want.splits > 0) {
+    int s = want.splits < n_tiles ? want.splits : n_tiles;
+    while (s > 1 && (int64_t)(s - 1) * ((n_tiles + s - 1) / s) >= n_tiles) --s;
+    want.splits = s;
+  }
+  AttnPlan best{want.waves ? want.waves : 4, want.splits ? want.splits : 1};
   double best_cost = 1e30;
   for (int nw = 4; nw <= 8; nw += 4) {
-    if ((forced_w == 4 || forced_w == 8) && nw != forced_w) continue;
+    if (want.waves && nw != want.waves) continue;
     const int bm = 32 * nw;
     const int slots = kCus * (8 / nw);
     const int64_t units = (int64_t)((n_q + bm - 1) / bm) * n_heads;
     for (int s = 1; s <= kMaxSplits && s <= n_tiles; ++s) {
       const int tiles_per = (n_tiles + s - 1) / s;
       if ((int64_t)(s - 1) * tiles_per >= n_tiles) continue;   // would leave an empty split
-      if (forced_s > 0 && s != forced_s && !(s == 1 && forced_s > n_tiles)) continue;
+      if (want.splits && s != want.splits) continue;
       const double rounds = (double)((units * s + slots - 1) / slots);
       double cost = rounds * tiles_per * (nw == 8 ? 0.96 : 1.0);
       if (s > 1) {
@@ -564,7 +566,7 @@ Plan choose_plan(int n_q, int n_heads, int64_t n_keys) {
         cost += 2.0 + (double)s * n_q * n_heads * 1040.0 / 8.4e6;
         cost *= 1.05;
       }
-      if (cost < best_cost - 1e-9) { best_cost = cost; best = Plan{nw, s}; }
+      if (cost < best_cost - 1e-9) { best_cost = cost; best = AttnPlan{nw, s}; }
     }
   }
   return best;
@@ -583,14 +585,18 @@ hipError_t launch_attention_t(const AttnArgs& a, SplitInfo sp, hipStream_t st) {
 
 }  // namespace
 
-size_t attention_workspace_bytes(int n_q, int n_heads, int64_t n_keys) {
-  const int s = choose_plan(n_q, n_heads, n_keys).splits;
+AttnPlan attention_plan(int n_q, int n_heads, int64_t n_keys, AttnPlan want) {
+  return choose_plan(n_q, n_heads, n_keys, want);
+}
+
+size_t attention_workspace_bytes(int n_q, int n_heads, int64_t n_keys, AttnPlan want) {
+  const int s = choose_plan(n_q, n_heads, n_keys, want).splits;
   if (s == 1) return 0;
   return (size_t)s * n_heads * n_q * (kHeadDim + 2) * sizeof(float);
 }
 
-hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
-  Plan plan = choose_plan(a.n_q, a.n_heads, a.n_keys);
+hipError_t launch_attention(const AttnArgs& a, AttnPlan want, hipStream_t st) {
+  AttnPlan plan = choose_plan(a.n_q, a.n_heads, a.n_keys, want);
   if (a.q_limit) plan.splits = 1;   // the per-query limits already shorten the key loops
   SplitInfo sp;
   sp.n_splits = plan.splits;

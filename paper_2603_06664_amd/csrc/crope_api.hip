@@ -86,6 +86,8 @@ int crope_qk_norm_rotate_append(
     return fail(CROPE_ESHAPE, "n_heads %d exceeds the supported maximum %d", n_heads,
                 crope::rope_max_heads());
   if (grid_h <= 0 || grid_w <= 0) return fail(CROPE_EINVAL, "grid sizes must be positive");
+  if ((int64_t)grid_h * grid_w > INT32_MAX)
+    return fail(CROPE_ERANGE, "grid_h * grid_w exceeds 2^31-1 tokens per frame");
   if (start_frame < 0 || token_offset < 0)
     return fail(CROPE_EINVAL, "start_frame and token_offset must be non-negative");
   if ((int64_t)token_offset + n_tokens > INT32_MAX)
@@ -140,18 +142,33 @@ int crope_qk_norm_rotate_append(
 
 size_t chunk_attention_workspace_bytes(int32_t n_q, int32_t n_heads, int64_t n_keys) {
   if (n_q <= 0 || n_heads <= 0 || n_keys <= 0) return 0;
-  return crope::attention_workspace_bytes(n_q, n_heads, n_keys);
+  return crope::attention_workspace_bytes(n_q, n_heads, n_keys, crope::AttnPlan{0, 0});
 }
 
 }  // extern "C"
 #pragma GCC visibility pop
 
 namespace {
+// 0 = ok and *want filled (zeros when plan is null)
+int check_plan(const crope_attention_plan* plan, crope::AttnPlan* want) {
+  *want = crope::AttnPlan{0, 0};
+  if (!plan) return CROPE_OK;
+  if (plan->waves != 0 && plan->waves != 4 && plan->waves != 8)
+    return fail(CROPE_EINVAL, "plan.waves must be 0, 4 or 8, got %d", plan->waves);
+  if (plan->splits < 0 || plan->splits > 16)
+    return fail(CROPE_EINVAL, "plan.splits must be 0..16, got %d", plan->splits);
+  *want = crope::AttnPlan{plan->waves, plan->splits};
+  return CROPE_OK;
+}
+
 int attention_impl(const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
                    const void* k_cache, const void* v_cache, crope_strides cache_strides,
                    int64_t cache_capacity_tokens, const crope_kv_segment* segs, int32_t n_segs,
-                   float scale, const int32_t* q_limit, bool limited, void* out, crope_strides out_strides,
+                   float scale, const int32_t* q_limit, bool limited, const crope_attention_plan* plan,
+                   void* out, crope_strides out_strides,
                    float* lse_or_null, void* workspace, size_t workspace_bytes, void* stream) {
+  crope::AttnPlan want;
+  if (int rc = check_plan(plan, &want)) return rc;
   if (limited && !q_limit) return fail(CROPE_EINVAL, "q_limit is null");
   if (limited && ((uintptr_t)q_limit & 3)) return fail(CROPE_EALIGN, "q_limit is not 4-byte aligned");
   if (!q || !k_cache || !v_cache || !out || !segs)
@@ -168,6 +185,9 @@ int attention_impl(const void* q, crope_strides q_strides, int32_t n_q, int32_t 
       !stride_ok(cache_strides.token) || !stride_ok(cache_strides.head) ||
       !stride_ok(out_strides.token) || !stride_ok(out_strides.head))
     return fail(CROPE_EALIGN, "strides must be positive multiples of 8 elements");
+  if (q_strides.head < crope::kHeadDim || out_strides.head < crope::kHeadDim ||
+      cache_strides.head < crope::kHeadDim)
+    return fail(CROPE_EINVAL, "head stride smaller than head_dim");
   if (cache_capacity_tokens <= 0) return fail(CROPE_EINVAL, "cache capacity must be positive");
   if (cache_capacity_tokens > INT32_MAX) return fail(CROPE_ERANGE, "cache capacity above 2^31-1 rows");
   if (cache_strides.token > (1 << 24)) return fail(CROPE_ERANGE, "cache token stride above 2^24 elements");
@@ -187,7 +207,7 @@ int attention_impl(const void* q, crope_strides q_strides, int32_t n_q, int32_t 
     a.segs.end[i] = (int32_t)n_keys;
   }
   for (int i = n_segs; i < crope::kMaxSegments; ++i) a.segs.base[i] = a.segs.base[n_segs - 1];
-  const size_t need = limited ? 0 : crope::attention_workspace_bytes(n_q > 0 ? n_q : 1, n_heads, n_keys);
+  const size_t need = limited ? 0 : crope::attention_workspace_bytes(n_q > 0 ? n_q : 1, n_heads, n_keys, want);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(CROPE_EWORKSPACE, "workspace has %zu bytes, needs %zu", workspace ? workspace_bytes : 0,
                 need);
@@ -200,7 +220,7 @@ int attention_impl(const void* q, crope_strides q_strides, int32_t n_q, int32_t 
   a.n_keys = n_keys; a.scale = scale;
   a.out = (uint16_t*)out; a.o_tok = out_strides.token; a.o_head = out_strides.head;
   a.lse = lse_or_null; a.workspace = workspace; a.workspace_bytes = workspace_bytes;
-  hipError_t e = crope::launch_attention(a, (hipStream_t)stream);
+  hipError_t e = crope::launch_attention(a, want, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "chunk_attention launch");
   g_err[0] = 0;
   return CROPE_OK;
@@ -216,7 +236,38 @@ int chunk_attention(const void* q, crope_strides q_strides, int32_t n_q, int32_t
                     float scale, void* out, crope_strides out_strides, float* lse_or_null,
                     void* workspace, size_t workspace_bytes, void* stream) {
   return attention_impl(q, q_strides, n_q, n_heads, k_cache, v_cache, cache_strides, cache_capacity_tokens,
-                        segs, n_segs, scale, nullptr, false, out, out_strides, lse_or_null, workspace,
+                        segs, n_segs, scale, nullptr, false, nullptr, out, out_strides, lse_or_null, workspace,
+                        workspace_bytes, stream);
+}
+
+int chunk_attention_choose_plan(int32_t n_q, int32_t n_heads, int64_t n_keys, crope_attention_plan* plan) {
+  if (!plan) return fail(CROPE_EINVAL, "plan is null");
+  if (n_q <= 0 || n_heads <= 0 || n_keys <= 0) return fail(CROPE_EINVAL, "sizes must be positive");
+  crope::AttnPlan want;
+  if (int rc = check_plan(plan, &want)) return rc;
+  const crope::AttnPlan p = crope::attention_plan(n_q, n_heads, n_keys, want);
+  plan->waves = p.waves;
+  plan->splits = p.splits;
+  g_err[0] = 0;
+  return CROPE_OK;
+}
+
+size_t chunk_attention_planned_workspace_bytes(int32_t n_q, int32_t n_heads, int64_t n_keys,
+                                               const crope_attention_plan* plan) {
+  if (n_q <= 0 || n_heads <= 0 || n_keys <= 0) return 0;
+  crope::AttnPlan want;
+  if (check_plan(plan, &want) != CROPE_OK) return 0;
+  return crope::attention_workspace_bytes(n_q, n_heads, n_keys, want);
+}
+
+int chunk_attention_planned(const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
+                            const void* k_cache, const void* v_cache, crope_strides cache_strides,
+                            int64_t cache_capacity_tokens, const crope_kv_segment* segs, int32_t n_segs,
+                            float scale, const crope_attention_plan* plan, void* out,
+                            crope_strides out_strides, float* lse_or_null, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  return attention_impl(q, q_strides, n_q, n_heads, k_cache, v_cache, cache_strides, cache_capacity_tokens,
+                        segs, n_segs, scale, nullptr, false, plan, out, out_strides, lse_or_null, workspace,
                         workspace_bytes, stream);
 }
 
@@ -226,7 +277,8 @@ int chunk_attention_limited(const void* q, crope_strides q_strides, int32_t n_q,
                             float scale, const int32_t* q_limit, void* out, crope_strides out_strides,
                             float* lse_or_null, void* stream) {
   return attention_impl(q, q_strides, n_q, n_heads, k_cache, v_cache, cache_strides, cache_capacity_tokens,
-                        segs, n_segs, scale, q_limit, true, out, out_strides, lse_or_null, nullptr, 0, stream);
+                        segs, n_segs, scale, q_limit, true, nullptr, out, out_strides, lse_or_null, nullptr, 0,
+                        stream);
 }
 
 size_t crope_qkv_project_workspace_bytes(int32_t n_tokens, int32_t n_heads, int32_t norm_group) {
@@ -255,6 +307,8 @@ int crope_qkv_project_norm_rotate_append(
     return fail(CROPE_ESHAPE, "c_in must be a positive multiple of 64, got %d", c_in);
   if (c_in > (1 << 20)) return fail(CROPE_ERANGE, "c_in above 2^20");
   if (grid_h <= 0 || grid_w <= 0) return fail(CROPE_EINVAL, "grid sizes must be positive");
+  if ((int64_t)grid_h * grid_w > INT32_MAX)
+    return fail(CROPE_ERANGE, "grid_h * grid_w exceeds 2^31-1 tokens per frame");
   if (start_frame < 0 || token_offset < 0)
     return fail(CROPE_EINVAL, "start_frame and token_offset must be non-negative");
   if ((int64_t)token_offset + n_tokens > INT32_MAX)
@@ -272,7 +326,8 @@ int crope_qkv_project_norm_rotate_append(
       !stride_ok(cache_strides.token) || !stride_ok(cache_strides.head))
     return fail(CROPE_EALIGN, "strides must be positive multiples of 8 elements");
   if (x_token_stride < c_in) return fail(CROPE_EINVAL, "x_token_stride smaller than c_in");
-  if (x_token_stride > (1 << 24)) return fail(CROPE_ERANGE, "x_token_stride above 2^24 elements");
+  // the kernel forms (row in tile) * stride * 2 bytes in 32 bits, rows up to 255
+  if (x_token_stride > (1 << 22)) return fail(CROPE_ERANGE, "x_token_stride above 2^22 elements");
   if (q_out_strides.head < crope::kHeadDim || cache_strides.head < crope::kHeadDim)
     return fail(CROPE_EINVAL, "head stride smaller than head_dim");
   if (grid_h > desc->max_h || grid_w > desc->max_w)
@@ -307,6 +362,7 @@ int crope_qkv_project_norm_rotate_append(
   a.c_tok = cache_strides.token; a.c_head = cache_strides.head;
   a.dst_token = dst_token;
   a.sumsq = (float*)workspace;
+  a.resid = nullptr;
   hipError_t e = crope::launch_project(a, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e, "crope_qkv_project_norm_rotate_append launch");
   g_err[0] = 0;

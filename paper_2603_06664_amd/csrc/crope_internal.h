@@ -72,13 +72,17 @@ struct ProjArgs {
   uint16_t *k_cache, *v_cache; int64_t c_tok, c_head;
   int64_t dst_token;
   float* sumsq;                       // [2][n_tokens][H] (row-wide norm only)
+  uint16_t* resid;                    // [2][n_tokens][H][128] bf16 low parts (row-wide norm only)
 };
 
 hipError_t launch_build_table(const crope_table_desc& d, float* table, hipStream_t st);
 hipError_t launch_rope(const RopeArgs& a, hipStream_t st);
 int rope_max_heads();
-hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
-size_t attention_workspace_bytes(int n_q, int n_heads, int64_t n_keys);
+// waves per work-group (4 or 8) and key splits (1..16); 0 = let the library choose
+struct AttnPlan { int waves; int splits; };
+AttnPlan attention_plan(int n_q, int n_heads, int64_t n_keys, AttnPlan want);
+hipError_t launch_attention(const AttnArgs& a, AttnPlan want, hipStream_t st);
+size_t attention_workspace_bytes(int n_q, int n_heads, int64_t n_keys, AttnPlan want);
 hipError_t launch_project(const ProjArgs& a, hipStream_t st);
 size_t project_workspace_bytes(int n_tokens, int n_heads, bool per_head_norm);
 

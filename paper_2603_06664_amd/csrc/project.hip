@@ -19,8 +19,11 @@
 //
 // RMSNorm over one head is local to the tile and fully fused.  RMSNorm over the token's
 // whole H*128 vector needs every head's sum of squares: the rotation commutes with the
-// per-token scalar, so the epilogue stores rotate(gain * y) and the per-head sums of
-// squares, and a second, bandwidth-bound pass multiplies q and k rows by 1/rms in place.
+// per-token scalar, so the epilogue stores z = rotate(gain * y) and the per-head sums of
+// squares, and a second, bandwidth-bound pass multiplies q and k rows by 1/rms.  z is kept
+// as TWO bf16 numbers, hi = bf16(z) in the destination row and lo = bf16(z - hi) in the
+// workspace (16 mantissa bits together), so that the second pass rounds (hi + lo) / rms to
+// bf16 once: the stored result is the single rounding of the fp32 value up to 2^-17 relative.
 #include "crope_internal.h"
 
 namespace crope {
@@ -80,12 +83,13 @@ struct TileLoader {   // scalars only
 // offsets are formed); their results are never stored.
 // The copy is inline assembly, not the compiler's builtin: while a builtin copy is in flight
 // the compiler turns every counted wait on an LDS read into a wait for all of them.  LDS
-// address of lane i's 16 bytes: M0 + 16*i.
+// address of lane i's 16 bytes: M0 + 16*i; M0 is an input operand bound to that register, the
+// s_nop is the wait state required between its write and the copy.
 __device__ __forceinline__ void copy16(const uint8_t* base /* wave-uniform */, uint32_t lane_off,
                                        uint8_t* lds_dst /* wave-uniform */) {
   const uint32_t m0 = __builtin_amdgcn_readfirstlane(LDS_ADDR(lds_dst));
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(lane_off), "s"(base), "s"(m0) : "memory");
+  asm volatile("s_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(lane_off), "s"(base), "{m0}"(m0) : "memory");
 }
 
 // PART 0, 1, 2: the W tile, the first and the second half of the x tile (two copies each); a
@@ -322,7 +326,8 @@ void qkv_project_kernel(ProjArgs a, ProjTiles pt) {
           acc[c][t][4 * b + 2] += bv[c][b].z; acc[c][t][4 * b + 3] += bv[c][b].w;
         }
   }
-  uint32_t packed[2][2][4][2];   // [t][c][b][pair of the 4 channels]
+  uint32_t packed[2][2][4][2];      // [t][c][b][pair of the 4 channels]
+  uint32_t packed_lo[2][2][4][2];   // row-wide norm: bf16 of what the first rounding dropped
 
   if (which == 2) {   // v: one rounding
 #pragma unroll
@@ -413,8 +418,15 @@ void qkv_project_kernel(ProjArgs a, ProjTiles pt) {
           const float4 cs = *reinterpret_cast<const float4*>(ang_lane + 32 * t * kAngRowB + (16 * c + 4 * b) * 8);
           const float xa0 = acc[c][t][4 * b + 0] * r[t] * gv[c][b].x, xb0 = acc[c][t][4 * b + 1] * r[t] * gv[c][b].y;
           const float xa1 = acc[c][t][4 * b + 2] * r[t] * gv[c][b].z, xb1 = acc[c][t][4 * b + 3] * r[t] * gv[c][b].w;
-          packed[t][c][b][0] = pack_bf16x2(xa0 * cs.x - xb0 * cs.y, xa0 * cs.y + xb0 * cs.x);
-          packed[t][c][b][1] = pack_bf16x2(xa1 * cs.z - xb1 * cs.w, xa1 * cs.w + xb1 * cs.z);
+          const float z0 = xa0 * cs.x - xb0 * cs.y, z1 = xa0 * cs.y + xb0 * cs.x;
+          const float z2 = xa1 * cs.z - xb1 * cs.w, z3 = xa1 * cs.w + xb1 * cs.z;
+          const uint32_t h0 = pack_bf16x2(z0, z1), h1 = pack_bf16x2(z2, z3);
+          packed[t][c][b][0] = h0;
+          packed[t][c][b][1] = h1;
+          if (!PER_HEAD) {
+            packed_lo[t][c][b][0] = pack_bf16x2(z0 - bf16_lo(h0), z1 - bf16_hi(h0));
+            packed_lo[t][c][b][1] = pack_bf16x2(z2 - bf16_lo(h1), z3 - bf16_hi(h1));
+          }
         }
       }
     __syncthreads();   // every wave has read its angles: the output tile may overwrite them
@@ -452,11 +464,37 @@ void qkv_project_kernel(ProjArgs a, ProjTiles pt) {
     }
   }
   __syncthreads();   // the output tile has been read: the next tile's copies may overwrite it
+  if (!PER_HEAD && which != 2) {
+    // the low parts take the same way out, into the workspace rows [which][token][head][128]
+    uint8_t* out_lane = out_lds + (64 * wt + n) * kOutRowB + (64 * wc + 4 * g) * 2;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          *reinterpret_cast<uint2*>(out_lane + 32 * t * kOutRowB + (32 * c + 8 * b) * 2) =
+              make_uint2(packed_lo[t][c][b][0], packed_lo[t][c][b][1]);
+    __syncthreads();
+    uint16_t* base = a.resid + ((int64_t)which * a.n_tokens * a.n_heads + head) * kHeadDim;
+    const int64_t tstride = (int64_t)a.n_heads * kHeadDim;
+    const int chunk = tid & 15;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int row = (tid >> 4) + 32 * it;
+      const int token = tok0 + row;
+      if (token < a.n_tokens)
+        *reinterpret_cast<uint4*>(base + (int64_t)token * tstride + chunk * 8) =
+            *reinterpret_cast<const uint4*>(out_lds + row * kOutRowB + chunk * 16);
+    }
+    __syncthreads();
+  }
   }   // next unit
 }
 
 // Second pass of the row-wide norm: one wave per (tensor, token) sums the per-head sums of
-// squares in a fixed order, and multiplies the stored rotate(gain * y) row by 1/rms in place.
+// squares in a fixed order, and replaces the stored high part of rotate(gain * y) by the bf16
+// rounding of (high + low) / rms.
 constexpr int kScaleWaves = 4;
 __global__ __launch_bounds__(64 * kScaleWaves) void scale_rows_kernel(ProjArgs a) {
   const int lane = threadIdx.x & 63;
@@ -469,26 +507,36 @@ __global__ __launch_bounds__(64 * kScaleWaves) void scale_rows_kernel(ProjArgs a
   const float r = 1.0f / sqrtf(s * (1.0f / (float)(a.n_heads * kHeadDim)) + a.eps);
   uint16_t* row = which == 0 ? a.q_out + (int64_t)tok * a.qo_tok : a.k_cache + (a.dst_token + tok) * a.c_tok;
   const int64_t hstride = which == 0 ? a.qo_head : a.c_head;
+  const uint16_t* lo_row = a.resid + ((int64_t)which * a.n_tokens + tok) * a.n_heads * kHeadDim;
   const int n_chunks = a.n_heads * 16;
   for (int c = lane; c < n_chunks; c += 64) {
     uint4* p = reinterpret_cast<uint4*>(row + (int64_t)(c >> 4) * hstride + (c & 15) * 8);
     uint4 u = *p;
-    u.x = pack_bf16x2(bf16_lo(u.x) * r, bf16_hi(u.x) * r);
-    u.y = pack_bf16x2(bf16_lo(u.y) * r, bf16_hi(u.y) * r);
-    u.z = pack_bf16x2(bf16_lo(u.z) * r, bf16_hi(u.z) * r);
-    u.w = pack_bf16x2(bf16_lo(u.w) * r, bf16_hi(u.w) * r);
+    const uint4 w = *reinterpret_cast<const uint4*>(lo_row + (int64_t)c * 8);
+    u.x = pack_bf16x2((bf16_lo(u.x) + bf16_lo(w.x)) * r, (bf16_hi(u.x) + bf16_hi(w.x)) * r);
+    u.y = pack_bf16x2((bf16_lo(u.y) + bf16_lo(w.y)) * r, (bf16_hi(u.y) + bf16_hi(w.y)) * r);
+    u.z = pack_bf16x2((bf16_lo(u.z) + bf16_lo(w.z)) * r, (bf16_hi(u.z) + bf16_hi(w.z)) * r);
+    u.w = pack_bf16x2((bf16_lo(u.w) + bf16_lo(w.w)) * r, (bf16_hi(u.w) + bf16_hi(w.w)) * r);
     *p = u;
   }
 }
 
 }  // namespace
 
+// fp32 sums of squares [2][tokens][heads], rounded up to 256 bytes, then the bf16 low parts
+// [2][tokens][heads][128]
+static size_t sumsq_bytes(int n_tokens, int n_heads) {
+  return (((size_t)2 * n_tokens * n_heads * sizeof(float)) + 255) & ~(size_t)255;
+}
 size_t project_workspace_bytes(int n_tokens, int n_heads, bool per_head_norm) {
   if (per_head_norm || n_tokens <= 0) return 0;
-  return (size_t)2 * n_tokens * n_heads * sizeof(float);
+  return sumsq_bytes(n_tokens, n_heads) + (size_t)2 * n_tokens * n_heads * kHeadDim * sizeof(uint16_t);
 }
 
-hipError_t launch_project(const ProjArgs& a, hipStream_t st) {
+hipError_t launch_project(const ProjArgs& a_in, hipStream_t st) {
+  ProjArgs a = a_in;
+  if (!a.per_head_norm)
+    a.resid = reinterpret_cast<uint16_t*>(reinterpret_cast<uint8_t*>(a.sumsq) + sumsq_bytes(a.n_tokens, a.n_heads));
   ProjTiles pt;
   pt.ch_tiles = 3 * a.n_heads;
   pt.tok_tiles = (a.n_tokens + kTileTok - 1) / kTileTok;

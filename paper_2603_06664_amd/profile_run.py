@@ -1,79 +1,113 @@
-"""Workload for rocprofv3: a few launches of each hot-path kernel at a benchmark shape, plus
-one plain device copy of known size that calibrates the HBM byte counters.
+"""Workload for rocprofv3: the benchmark's own step, on the benchmark's own inputs.
+
+The inputs, the cache contents, the launch arguments and the warm-up are those of bench.py
+(workloads.make_inputs + devutil.StepBuffers; 15 set-up steps, then --warmup steps), followed
+by --steps profiled steps of crope_qk_norm_rotate_append + chunk_attention, a few launches of
+the fused projection entry point, and one plain device copy of known size that calibrates the
+HBM byte counters.
 
   rocprofv3 --kernel-trace --stats --output-format csv -d OUT -- python3 -m paper_2603_06664_amd.profile_run
   rocprofv3 --pmc FETCH_SIZE --output-format csv -d OUT -- python3 -m paper_2603_06664_amd.profile_run
   rocprofv3 --pmc WRITE_SIZE --output-format csv -d OUT -- python3 -m paper_2603_06664_amd.profile_run
 
-Inputs are random bf16 tensors of the workload's shape (values do not matter for byte or
-duration counters); the append kernel rotates over disjoint input sets so that its reads
-come from HBM rather than from the last-level cache.
+The profiler's own --stats table averages over every launch, the cache fill and the cold first
+launches included.  `--summarize FILE.csv` reads a kernel-trace or counter-collection CSV
+written by one of the commands above and prints, per kernel, the figures of its LAST --steps
+launches only (the profiled steps), which is what the benchmark's timed region corresponds to.
 """
 from __future__ import annotations
 
 import argparse
-
-import torch
-
-from . import binding as P
-from .workloads import CONFIGS
+import csv
+import sys
 
 COPY_BYTES = 1 << 30
+SETUP_STEPS = 15
+
+
+def summarize(path: str, last: int) -> None:
+    rows = list(csv.DictReader(open(path, newline="")))
+    if not rows:
+        print("no rows in", path)
+        return
+    by = {}
+    if "Counter_Name" not in rows[0]:         # kernel trace
+        for r in rows:
+            by.setdefault(r["Kernel_Name"], []).append((int(r["Start_Timestamp"]), int(r["End_Timestamp"]) - int(r["Start_Timestamp"])))
+        print("kernel trace %s: duration of the last %d launches of each kernel, ns" % (path, last))
+        for name, v in sorted(by.items(), key=lambda kv: -sum(d for _, d in kv[1])):
+            v.sort()
+            d = sorted(x for _, x in v[-last:])
+            print("  %-90s launches %4d  mean %10.0f  median %10d  min %10d  max %10d"
+                  % (name[:90], len(v), sum(d) / len(d), d[len(d) // 2], d[0], d[-1]))
+    else:                                      # counter collection
+        for r in rows:
+            by.setdefault((r["Kernel_Name"], r["Counter_Name"]), []).append((int(r["Dispatch_Id"]), float(r["Counter_Value"])))
+        print("counters %s: mean over the last %d dispatches of each kernel" % (path, last))
+        for (name, ctr), v in sorted(by.items()):
+            v.sort()
+            d = [x for _, x in v[-last:]]
+            print("  %-90s %-24s dispatches %4d  mean %16.1f" % (name[:90], ctr, len(v), sum(d) / len(d)))
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="C4")
-    ap.add_argument("--iters", type=int, default=8)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--input-sets", type=int, default=8)
+    ap.add_argument("--projection-iters", type=int, default=8)
+    ap.add_argument("--summarize", metavar="CSV", default=None)
     args = ap.parse_args()
-    cfg = CONFIGS[args.workload]
-    H, D, n, nk = cfg.n_heads, cfg.head_dim, cfg.n_q, cfg.n_keys
-    dev = "cuda"
-    desc = P.TableDesc()
-    tab = torch.empty(P.crope_table_bytes(desc) // 4, dtype=torch.float32, device=dev)
-    P.crope_build_table(desc, tab)
+    if args.summarize:
+        summarize(args.summarize, args.steps)
+        return
+
+    import torch
+
+    from . import binding as P
+    from . import devutil, workloads as W
+
+    cfg = W.CONFIGS[args.workload]
+    H, D, n = cfg.n_heads, cfg.head_dim, cfg.n_q
+    inp = W.make_inputs(cfg)
+    sb = devutil.StepBuffers(cfg, inp, input_sets=args.input_sets)
     # calibration copy: reads COPY_BYTES and writes COPY_BYTES
-    src = torch.empty(COPY_BYTES, dtype=torch.uint8, device=dev).random_(0, 255)
+    src = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda").random_(0, 255)
     dst = torch.empty_like(src)
     dst.copy_(src)
     torch.cuda.synchronize()
-    sets = [tuple(torch.randn(n, H, D, device=dev, dtype=torch.bfloat16) for _ in range(3))
-            for _ in range(args.input_sets)]
-    gq = torch.ones(H * D, device=dev)
-    gk = torch.ones(H * D, device=dev)
-    cap = nk
-    k_cache = torch.randn(cap, H, D, device=dev, dtype=torch.bfloat16)
-    v_cache = torch.randn(cap, H, D, device=dev, dtype=torch.bfloat16)
-    q_rot = torch.empty(n, H, D, device=dev, dtype=torch.bfloat16)
-    out = torch.empty_like(q_rot)
-    ws_bytes = P.chunk_attention_workspace_bytes(n, H, nk)
-    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
-    dst_row = (cfg.start_frame - cfg.first_kv_frame) * cfg.hw + cfg.token_offset
+    del src, dst
+
+    # the fused projection entry point (both norm readings), model width c_in = H*128; before
+    # the steps, so that the steps' launches are the last ones of their kernels
+    if args.projection_iters > 0:
+        c_in = H * D
+        pin = W.make_projection_inputs(cfg)
+        w_qkv = devutil.to_dev_bf16(pin.w)
+        bias = torch.from_numpy(pin.bias).cuda()
+        xs = [devutil.to_dev_bf16(pin.x)]
+        for _ in range(3):
+            xs.append(xs[0].clone())
+        pws_bytes = P.crope_qkv_project_workspace_bytes(n, H, H * D)
+        pws = torch.empty(max(pws_bytes, 16), dtype=torch.uint8, device="cuda")
+        for grp in (D, H * D):
+            for i in range(args.projection_iters + 4):
+                P.crope_qkv_project_norm_rotate_append(sb.desc, sb.tab, xs[i % 4], w_qkv, bias, c_in, sb.gq, sb.gk,
+                                                       cfg.eps, grp, n, H, cfg.grid_h, cfg.grid_w, sb.s, sb.off,
+                                                       sb.q_rot, sb.k_cache, sb.v_cache, sb.cap, sb.dst, pws,
+                                                       pws_bytes)
+            torch.cuda.synchronize()
+
+    for i in range(SETUP_STEPS + args.warmup):
+        sb.step(i)
     torch.cuda.synchronize()
-    for i in range(args.iters):
-        q, k, v = sets[i % len(sets)]
-        P.crope_qk_norm_rotate_append(desc, tab, q, k, v, gq, gk, cfg.eps, H * D, n, H, cfg.grid_h,
-                                      cfg.grid_w, cfg.start_frame, cfg.token_offset, q_rot, k_cache,
-                                      v_cache, cap, dst_row)
-        P.chunk_attention(q_rot, n, H, k_cache, v_cache, cap, [(0, nk)], D ** -0.5, out, None, ws,
-                          ws_bytes)
-    # the fused projection entry point (both norm readings), model width c_in = H*128
-    c_in = H * D
-    xs = [torch.randn(n, c_in, device=dev, dtype=torch.bfloat16) for _ in range(4)]
-    w_qkv = (torch.randn(3 * H * D, c_in, device=dev) * c_in ** -0.5).to(torch.bfloat16)
-    bias = 0.1 * torch.randn(3 * H * D, device=dev)
-    pws_bytes = P.crope_qkv_project_workspace_bytes(n, H, H * D)
-    pws = torch.empty(max(pws_bytes, 16), dtype=torch.uint8, device=dev)
-    for i in range(args.iters):
-        grp = D if i % 2 == 0 else H * D
-        P.crope_qkv_project_norm_rotate_append(desc, tab, xs[i % 4], w_qkv, bias, c_in, gq, gk, cfg.eps, grp,
-                                               n, H, cfg.grid_h, cfg.grid_w, cfg.start_frame,
-                                               cfg.token_offset, q_rot, k_cache, v_cache, cap, dst_row, pws,
-                                               pws_bytes)
+    for i in range(args.steps):
+        sb.step(i)
     torch.cuda.synchronize()
-    print("profile_run done: %s, %d iterations, copy %d bytes" % (cfg.name, args.iters, COPY_BYTES))
+    print("profile_run done: %s, %d set-up + %d warm-up + %d profiled steps, copy %d bytes"
+          % (cfg.name, SETUP_STEPS, args.warmup, args.steps, COPY_BYTES))
 
 
 if __name__ == "__main__":
-    main()
+    sys.exit(main())

@@ -1,46 +1,52 @@
 """Shared test plumbing: runs one configuration through the HIP path (via the C-ABI
 binding) and through the CPU oracle on the same seeded inputs, and compares.
 
-Tolerances (bf16 outputs): max-abs <= 2e-2 and relative L2 <= 1e-2.  A bf16 number of
-magnitude >= 8 has a half-ulp of 2^-5 > 2e-2, so for tensors that can hold such values
-(rotated keys under a per-head gain scale) the element bound is 2e-2 + 2^-8*|oracle|:
-the stated absolute bound plus bf16's own worst-case rounding of the oracle value.
+Tolerances (bf16 outputs): relative L2 <= 1e-2 over a tensor and, per element,
+|got - oracle| <= 2e-2 wherever |oracle| < 8.  A bf16 number of magnitude >= 8 has a half-ulp
+of 2^-5 > 2e-2, so no single rounding of the oracle value can meet 2e-2 there; for those
+elements (rotated keys under a per-head gain scale) the bound is bf16's own half-ulp at the
+oracle value's binade, 2^(floor(log2|oracle|) - 8), plus 2^-18 * |oracle| for the fp32
+arithmetic in front of the rounding.
 """
 from __future__ import annotations
 
 import numpy as np
 
 from paper_2603_06664_amd import workloads as W
+from paper_2603_06664_amd.devutil import (  # noqa: F401  (re-exported for the tests)
+    SCALE, bits_to_f64, dev_bits, dst_row, make_table, to_dev_bf16, visible_segments)
 
 MAX_ABS = 2e-2
 REL_L2 = 1e-2
-SCALE = 128 ** -0.5
+LARGE = 8.0   # below this magnitude the flat 2e-2 bound applies
 
 
-def bits_to_f64(b: np.ndarray) -> np.ndarray:
-    return W.bf16_bits_to_f32(b).astype(np.float64)
+def element_bound(ref: np.ndarray) -> np.ndarray:
+    a = np.abs(np.asarray(ref, dtype=np.float64))
+    big = a >= LARGE
+    half_ulp = np.exp2(np.floor(np.log2(np.where(big, a, LARGE))) - 8.0)
+    return np.where(big, half_ulp + 2.0 ** -18 * a, MAX_ABS)
 
 
 def errors(got: np.ndarray, ref: np.ndarray):
+    """max-abs difference, relative L2, and the largest excess over the per-element bound
+    (<= 0 when every element is inside it)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     diff = np.abs(got - ref)
     max_abs = float(diff.max()) if diff.size else 0.0
     denom = float(np.sqrt((ref ** 2).sum()))
     rel_l2 = float(np.sqrt((diff ** 2).sum()) / denom) if denom > 0 else 0.0
-    excess = float((diff - (MAX_ABS + 2.0 ** -8 * np.abs(ref))).max()) if diff.size else -1.0
+    excess = float((diff - element_bound(ref)).max()) if diff.size else -1.0
     return max_abs, rel_l2, excess
 
 
-def assert_close(name, got, ref, strict_abs=True):
+def assert_close(name, got, ref):
     max_abs, rel_l2, excess = errors(got, ref)
     msg = "%s: max_abs=%.3e rel_l2=%.3e" % (name, max_abs, rel_l2)
     assert np.all(np.isfinite(np.asarray(got, dtype=np.float64))), msg + " (non-finite)"
     assert rel_l2 <= REL_L2, msg
-    if strict_abs:
-        assert max_abs <= MAX_ABS, msg
-    else:
-        assert excess <= 0.0, msg + " (beyond 2e-2 + 2^-8*|ref|)"
+    assert excess <= 0.0, msg + " (an element is %.3e beyond its bound: 2e-2 below |ref| = 8, bf16 half-ulp above)" % excess
     return max_abs, rel_l2
 
 
@@ -69,44 +75,7 @@ def oracle_chain(cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, q_rows
     return dict(q_rot=q_rot, k_cache=cache.k, v_cache=cache.v, segs=segs, o=o, lse=lse)
 
 
-def dst_row(cfg: W.ChunkConfig, start_frame: int, token_offset: int) -> int:
-    """Cache row where the call for (start_frame, token_offset) writes its first token."""
-    return W.cache_slot(cfg, start_frame) * cfg.hw + token_offset
-
-
-def visible_segments(cfg: W.ChunkConfig):
-    """Row segments holding frames first_kv_frame .. start_frame+n_frames-1, oldest first,
-    merged where slots are consecutive."""
-    segs = []
-    for f in range(cfg.first_kv_frame, cfg.start_frame + cfg.n_frames):
-        start = W.cache_slot(cfg, f) * cfg.hw
-        if segs and segs[-1][0] + segs[-1][1] == start:
-            segs[-1] = (segs[-1][0], segs[-1][1] + cfg.hw)
-        else:
-            segs.append((start, cfg.hw))
-    return segs
-
-
 # ------------------------------------------------------------------ HIP side
-def to_dev_bf16(bits: np.ndarray):
-    import torch
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
-
-
-def dev_bits(t) -> np.ndarray:
-    import torch
-    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
-
-
-def make_table(desc=None):
-    import torch
-    import paper_2603_06664_amd as P
-    desc = desc or P.TableDesc()
-    tab = torch.empty(P.crope_table_bytes(desc) // 4, dtype=torch.float32, device="cuda")
-    P.crope_build_table(desc, tab)
-    return desc, tab
-
-
 def hip_chain(cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, want_lse=True):
     """Runs table build, every append call of the schedule, then attention, through the
     C ABI.  Returns numpy results (bf16 bits widened to fp64 where noted)."""

@@ -91,6 +91,8 @@ def _append(desc=None, q_addr=A, n=24, H=2, gh=4, gw=6, s=5, off=0, cap=72, dst=
     (dict(off=24, desc=P.TableDesc(max_t=6)), B.CROPE_ERANGE),  # offset pushes rows into frame 6
     (dict(off=2**31 - 10, desc=P.TableDesc(max_t=1 << 20, max_h=1 << 10, max_w=1 << 11), gh=1 << 10,
           gw=1 << 11, s=0), B.CROPE_ERANGE),                    # 32-bit token index would wrap
+    (dict(desc=P.TableDesc(max_h=1 << 16, max_w=1 << 16), gh=1 << 16, gw=1 << 15),
+     B.CROPE_ERANGE),                                           # tokens per frame would not fit 32 bits
 ])
 def test_append_rejects_bad_arguments(kwargs, code):
     with pytest.raises(P.CropeError) as ei:
@@ -103,10 +105,14 @@ def test_append_zero_tokens_is_a_noop():
     _append(n=0, dst=72)   # valid: writes rows [72, 72)
 
 
-def _attn(n_q=24, H=2, cap=72, segs=((0, 72),), scale=128 ** -0.5, q_addr=A, ws=None, ws_bytes=0):
-    q = _FakeTensor(q_addr, (max(n_q, 1), H, 128))
-    c = _FakeTensor(A, (cap, H, 128))
-    P.chunk_attention(q, n_q, H, c, c, cap, list(segs), scale, q, None, ws, ws_bytes)
+def _attn(n_q=24, H=2, cap=72, segs=((0, 72),), scale=128 ** -0.5, q_addr=A, ws=None, ws_bytes=0,
+          q_strides=None, c_strides=None, plan=None):
+    q = _FakeTensor(q_addr, (max(n_q, 1), H, 128), q_strides)
+    c = _FakeTensor(A, (cap, H, 128), c_strides)
+    if plan is None:
+        P.chunk_attention(q, n_q, H, c, c, cap, list(segs), scale, q, None, ws, ws_bytes)
+    else:
+        P.chunk_attention_planned(q, n_q, H, c, c, cap, list(segs), scale, plan, q, None, ws, ws_bytes)
 
 
 @pytest.mark.parametrize("kwargs,code", [
@@ -120,6 +126,12 @@ def _attn(n_q=24, H=2, cap=72, segs=((0, 72),), scale=128 ** -0.5, q_addr=A, ws=
     (dict(q_addr=A + 8), B.CROPE_EALIGN),
     (dict(n_q=-3), B.CROPE_EINVAL),
     (dict(H=0), B.CROPE_EINVAL),
+    (dict(q_strides=[128, 64, 1]), B.CROPE_EINVAL),      # heads would overlap
+    (dict(c_strides=[256, 120, 1]), B.CROPE_EINVAL),
+    (dict(plan=(3, 0)), B.CROPE_EINVAL),                 # 4 or 8 waves
+    (dict(plan=(8, 17)), B.CROPE_EINVAL),
+    (dict(plan=(0, -1)), B.CROPE_EINVAL),
+    (dict(n_q=4680, cap=32760, segs=((0, 32760),), H=12, plan=(4, 2)), B.CROPE_EWORKSPACE),
 ])
 def test_attention_rejects_bad_arguments(kwargs, code):
     with pytest.raises(P.CropeError) as ei:
@@ -134,6 +146,29 @@ def test_attention_zero_queries_is_a_noop():
 def test_workspace_size_query():
     assert P.chunk_attention_workspace_bytes(0, 12, 100) == 0
     assert P.chunk_attention_workspace_bytes(4680, 12, 32760) >= 0
+
+
+def test_plan_queries_are_pure_functions_of_their_arguments(monkeypatch):
+    # no environment variable or earlier call changes a plan
+    monkeypatch.setenv("CROPE_ATTN_SPLITS", "7")
+    monkeypatch.setenv("CROPE_ATTN_WAVES", "4")
+    auto = P.chunk_attention_choose_plan(4680, 12, 32760)
+    assert auto == P.chunk_attention_choose_plan(4680, 12, 32760, (0, 0))
+    assert auto[0] in (4, 8) and 1 <= auto[1] <= 16
+    assert P.chunk_attention_workspace_bytes(4680, 12, 32760) == \
+        P.chunk_attention_planned_workspace_bytes(4680, 12, 32760, auto) == \
+        P.chunk_attention_planned_workspace_bytes(4680, 12, 32760, None)
+    # a pinned field is kept, the other one chosen
+    assert P.chunk_attention_choose_plan(4680, 12, 32760, (4, 0))[0] == 4
+    assert P.chunk_attention_choose_plan(4680, 12, 32760, (0, 3))[1] == 3
+    # fp32 partial O (128) plus reference maximum and denominator per query, head and split
+    assert P.chunk_attention_planned_workspace_bytes(100, 3, 1000, (4, 3)) == 3 * 3 * 100 * 130 * 4
+    # more splits than key tiles: lowered until no split is empty (130 keys = 3 tiles)
+    assert P.chunk_attention_choose_plan(50, 2, 130, (4, 16)) == (4, 3)
+    assert P.chunk_attention_choose_plan(50, 2, 64 * 5, (8, 4)) == (8, 3)   # 5 tiles in 4 splits of 2 leaves one empty
+    with pytest.raises(P.CropeError):
+        P.chunk_attention_choose_plan(0, 2, 130)
+    assert P.chunk_attention_planned_workspace_bytes(100, 3, 1000, (5, 3)) == 0   # invalid plan
 
 
 def test_build_table_rejects_small_buffer():
@@ -151,7 +186,7 @@ class _FakeMatrix(_FakeTensor):
 
 
 def _project(n=24, H=2, c_in=256, x_addr=A, w_addr=A, x_stride=None, cap=72, dst=48, group=256, ws=A,
-             ws_bytes=1 << 20, desc=None, gh=4, gw=6, s=5):
+             ws_bytes=1 << 26, desc=None, gh=4, gw=6, s=5):
     desc = desc or P.TableDesc()
     x = _FakeMatrix(x_addr, (n, c_in), [c_in if x_stride is None else x_stride, 1])
     w = _FakeMatrix(w_addr, (3 * H * 128, c_in))
@@ -171,6 +206,7 @@ def _project(n=24, H=2, c_in=256, x_addr=A, w_addr=A, x_stride=None, cap=72, dst
     (dict(w_addr=0), B.CROPE_EINVAL),
     (dict(x_stride=128), B.CROPE_EINVAL),            # row stride smaller than c_in
     (dict(x_stride=260), B.CROPE_EALIGN),            # rows not 16-byte aligned
+    (dict(x_stride=(1 << 22) + 8), B.CROPE_ERANGE),  # 32-bit byte offsets inside a tile would wrap
     (dict(dst=49), B.CROPE_ERANGE),
     (dict(group=64), B.CROPE_EINVAL),
     (dict(ws=None), B.CROPE_EWORKSPACE),             # the row-wide norm needs its scratch
@@ -188,5 +224,7 @@ def test_project_rejects_bad_arguments(kwargs, code):
 def test_project_zero_tokens_is_a_noop_and_workspace_sizes():
     _project(n=0, dst=72)
     assert P.crope_qkv_project_workspace_bytes(4680, 12, 128) == 0
-    assert P.crope_qkv_project_workspace_bytes(4680, 12, 1536) == 2 * 4680 * 12 * 4
+    # sums of squares (rounded up to 256 B) + the bf16 low parts of q and k
+    assert P.crope_qkv_project_workspace_bytes(4680, 12, 1536) == 2 * 4680 * 12 * 4 + 2 * 4680 * 12 * 128 * 2
+    assert P.crope_qkv_project_workspace_bytes(3, 3, 384) == 256 + 2 * 3 * 3 * 128 * 2
     assert P.crope_qkv_project_workspace_bytes(0, 12, 1536) == 0

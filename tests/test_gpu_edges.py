@@ -1,8 +1,6 @@
 """Edge cases of the HIP path against the fp64 oracle: many segments, ragged tiles, extreme
 logits, head counts at the limits, far time positions, and the non-default work-group shapes."""
 import os
-import subprocess
-import sys
 
 import numpy as np
 import pytest
@@ -55,6 +53,10 @@ def _attn_case(P, n_q, H, cap, segs, seed, q_scale=1.0, want_lse=True):
     [(10, 63), (200, 1)],                           # 64 keys split 63 + 1 across a tile
     [(5, 64), (100, 64), (300, 64)],                # tile-aligned lengths, unaligned starts
     [(0, 1), (1, 1), (2, 1), (3, 1)],               # four one-key segments
+    # key 0 -> row 100 and key 63 -> row 163 are 63 rows apart, but the rows between them are
+    # not consecutive (keys 32..47 live in rows 0..15): the tile must not be copied as one run
+    [(100, 32), (0, 16), (148, 16)],
+    [(64, 16), (0, 32), (112, 16), (200, 70)],      # the same trap with a fourth segment behind it
 ])
 def test_attention_segment_shapes(P, segs):
     print("case segs", segs, flush=True)
@@ -159,32 +161,39 @@ def test_rope_rejects_frame_beyond_table(P):
     assert ei.value.code == -4
 
 
-_VARIANT_SCRIPT = r"""
-import sys, numpy as np
-sys.path.insert(0, %(root)r); sys.path.insert(0, %(root)r + "/tests")
-from paper_2603_06664_amd import workloads as W
-import harness as Hn
-for cfg in (W.ChunkConfig("V1", 71, 3, 9, 11, start_frame=6, n_frames=3, first_kv_frame=0),
-            W.ChunkConfig("V2", 72, 2, 4, 6, start_frame=7, n_frames=1, first_kv_frame=5, cache_frames=3)):
-    inp = W.make_inputs(cfg)
-    ref = Hn.oracle_chain(cfg, inp); got = Hn.hip_chain(cfg, inp)
-    Hn.assert_close("o", got["o"], ref["o"])
-    assert np.max(np.abs(got["lse"] - ref["lse"])) <= 2e-2
-print("variant ok")
-"""
-
-
-@pytest.mark.parametrize("env", [{"CROPE_ATTN_WAVES": "4"}, {"CROPE_ATTN_WAVES": "8"},
-                                 {"CROPE_ATTN_WAVES": "4", "CROPE_ATTN_SPLITS": "3"},
-                                 {"CROPE_ATTN_WAVES": "8", "CROPE_ATTN_SPLITS": "7"}])
-def test_forced_plans_in_a_child_process(env):
-    """The work-group shape and the key split are normally chosen by the library; force the
-    other shapes (the knobs are read once per process, hence the child)."""
-    e = dict(os.environ)
-    e.update(env)
-    r = subprocess.run([sys.executable, "-c", _VARIANT_SCRIPT % {"root": ROOT}], env=e, capture_output=True,
-                       text=True, timeout=110)
-    assert r.returncode == 0 and "variant ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+@pytest.mark.parametrize("plan", [(4, 0), (8, 0), (4, 3), (8, 7), (0, 2), (4, 16)])
+def test_forced_plans(P, plan):
+    """The work-group shape and the key split are normally chosen by the library; reach the
+    other shapes through chunk_attention_planned and compare each with the oracle."""
+    import torch
+    for cfg in (W.ChunkConfig("V1", 71, 3, 9, 11, start_frame=6, n_frames=3, first_kv_frame=0),
+                W.ChunkConfig("V2", 72, 2, 4, 6, start_frame=7, n_frames=1, first_kv_frame=5, cache_frames=3)):
+        print("case", cfg.name, "plan", plan, flush=True)
+        inp = W.make_inputs(cfg)
+        ref = Hn.oracle_chain(cfg, inp)
+        from paper_2603_06664_amd.devutil import StepBuffers
+        sb = StepBuffers(cfg, inp)
+        sb.append()
+        resolved = P.chunk_attention_choose_plan(cfg.n_q, cfg.n_heads, sb.n_keys, plan)
+        assert resolved[0] in (4, 8) and 1 <= resolved[1] <= 16
+        if plan[0]:
+            assert resolved[0] == plan[0]
+        n_tiles = (sb.n_keys + 63) // 64
+        if plan[1]:
+            assert resolved[1] == plan[1] or plan[1] > n_tiles or (plan[1] - 1) * -(-n_tiles // plan[1]) >= n_tiles
+        wsb = P.chunk_attention_planned_workspace_bytes(cfg.n_q, cfg.n_heads, sb.n_keys, plan)
+        assert (wsb == 0) == (resolved[1] == 1)
+        ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        P.chunk_attention_planned(sb.q_rot, cfg.n_q, cfg.n_heads, sb.k_cache, sb.v_cache, sb.cap, sb.segs,
+                                  Hn.SCALE, plan, sb.out, sb.lse, ws, wsb)
+        torch.cuda.synchronize()
+        Hn.assert_close("o", Hn.bits_to_f64(Hn.dev_bits(sb.out)), ref["o"])
+        assert np.max(np.abs(sb.lse.cpu().numpy().astype(np.float64) - ref["lse"])) <= 2e-2
+        if wsb:   # a split plan with too little workspace is refused
+            with pytest.raises(P.CropeError) as ei:
+                P.chunk_attention_planned(sb.q_rot, cfg.n_q, cfg.n_heads, sb.k_cache, sb.v_cache, sb.cap,
+                                          sb.segs, Hn.SCALE, plan, sb.out, sb.lse, ws, wsb - 16)
+            assert ei.value.code == -5
 
 
 def _limited_case(P, n_q, H, n_k, limits, seed):

@@ -1,8 +1,9 @@
 """Parity of the HIP path (through the C ABI) against the fp64 CPU oracle.
 
-Small shapes are compared element by element on every output; the full-size benchmark
-configurations compare every element of the rotated q, rotated-k cache and v cache, and
-the attention output on a sample of query rows that covers tile edges.
+Small shapes are compared element by element on every output; so are the full-size
+benchmark configurations (rotated q, rotated-k cache, v cache, attention output and LSE of
+every query row), except the 960x1664 workload, whose attention output is compared on a
+sample of query rows that covers tile edges (the oracle would need minutes for all of it).
 """
 import dataclasses
 
@@ -76,8 +77,8 @@ def test_small_config_every_element(P, cfg, per_head):
     ref = Hn.oracle_chain(cfg, inp, norm_group=group)
     got = Hn.hip_chain(cfg, inp, norm_group=group)
     assert got["segs"] == ref["segs"]
-    Hn.assert_close("q_rot", got["q_rot"], ref["q_rot"], strict_abs=not cfg.k_head_scale)
-    Hn.assert_close("k_cache", got["k_cache"], ref["k_cache"], strict_abs=not cfg.k_head_scale)
+    Hn.assert_close("q_rot", got["q_rot"], ref["q_rot"])
+    Hn.assert_close("k_cache", got["k_cache"], ref["k_cache"])
     # v is a copy: bit-exact
     v_ref = np.zeros_like(got["v_cache_bits"])
     for (s, nf, row0, n, off, _) in W.chunk_schedule(cfg):
@@ -102,15 +103,15 @@ def test_full_size_config(P, name):
     cfg = W.CONFIGS[name]
     _say("case %s: n_q=%d n_keys=%d heads=%d" % (name, cfg.n_q, cfg.n_keys, cfg.n_heads))
     inp = W.make_inputs(cfg)
-    rows = _sample_rows(cfg.n_q, np.random.default_rng(100 + cfg.seed))
+    # every query row; only the largest workload is sampled
+    rows = _sample_rows(cfg.n_q, np.random.default_rng(100 + cfg.seed)) if name == "R960" else list(range(cfg.n_q))
     got = Hn.hip_chain(cfg, inp)
     _say("  hip path done")
     ref = Hn.oracle_chain(cfg, inp, q_rows=rows)
-    _say("  oracle done")
-    loose = cfg.k_head_scale
-    e = Hn.assert_close("q_rot", got["q_rot"], ref["q_rot"], strict_abs=True)
+    _say("  oracle done (%d of %d query rows)" % (len(rows), cfg.n_q))
+    e = Hn.assert_close("q_rot", got["q_rot"], ref["q_rot"])
     _say("  q_rot   max_abs %.3e rel_l2 %.3e" % e)
-    e = Hn.assert_close("k_cache", got["k_cache"], ref["k_cache"], strict_abs=not loose)
+    e = Hn.assert_close("k_cache", got["k_cache"], ref["k_cache"])
     _say("  k_cache max_abs %.3e rel_l2 %.3e" % e)
     v_ref = np.zeros_like(got["v_cache_bits"])
     for (s_, nf, row0, n, off, _) in W.chunk_schedule(cfg):
