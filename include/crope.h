@@ -183,6 +183,31 @@ int chunk_attention_planned(
     void* out, crope_strides out_strides, float* lse_or_null,
     void* workspace, size_t workspace_bytes, void* stream);
 
+/* chunk_attention for callers that cannot allocate device memory or carry a workspace around
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * scratch for the partial results of a split key range is a buffer of
+ * CROPE_STATIC_SCRATCH_BYTES built into the library, one copy per GPU, held from the moment the
+ * library is loaded on that GPU until the process ends.  The call allocates and frees nothing.
+ * Same arguments, same kernels, same work division and bit-identical results as
+ * chunk_attention, minus workspace / workspace_bytes.
+ *   - CROPE_EWORKSPACE, before anything is launched, if the problem would need more scratch
+ *     than the buffer holds (chunk_attention_workspace_bytes(...) > CROPE_STATIC_SCRATCH_BYTES);
+ *     the 40-head 585-query x 32760-key rank share needs 58 MiB.
+ *   - The first call on a GPU looks the buffer's device address up (a runtime query, no
+ *     allocation) and keeps it for later calls; call with that GPU current.  Make that first
+ *     call outside any graph capture.
+ *   - Every call on a GPU shares that GPU's buffer.  Nothing in it needs clearing between
+ *     calls (each partial result is written before it is read), but two calls whose work
+ *     overlaps in time on one GPU (different streams) race on it: serialise them. */
+#define CROPE_STATIC_SCRATCH_BYTES (64u << 20)
+size_t chunk_attention_static_capacity(void);   /* == CROPE_STATIC_SCRATCH_BYTES */
+int chunk_attention_static(
+    const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
+    const void* k_cache, const void* v_cache, crope_strides cache_strides,
+    int64_t cache_capacity_tokens,
+    const crope_kv_segment* segs, int32_t n_segs, float scale,
+    void* out, crope_strides out_strides, float* lse_or_null, void* stream);
+
 /* chunk_attention with a per-query prefix limit: query i attends only to the first
  * q_limit[i] rows of the visible set (rows counted in the order of `segs`).  With keys laid
  * out in generation order this is the block-causal rule of the generator itself (Section

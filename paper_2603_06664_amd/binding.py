@@ -101,6 +101,12 @@ def _load():
     lib.chunk_attention_planned.argtypes = [
         vp, _Strides, i32, i32, vp, vp, _Strides, i64, ctypes.POINTER(_Segment), i32, f32,
         ctypes.POINTER(_Plan), vp, _Strides, vp, vp, ctypes.c_size_t, vp]
+    lib.chunk_attention_static_capacity.restype = ctypes.c_size_t
+    lib.chunk_attention_static_capacity.argtypes = []
+    lib.chunk_attention_static.restype = ctypes.c_int
+    lib.chunk_attention_static.argtypes = [
+        vp, _Strides, i32, i32, vp, vp, _Strides, i64, ctypes.POINTER(_Segment), i32, f32, vp,
+        _Strides, vp, vp]
     lib.chunk_attention_limited.restype = ctypes.c_int
     lib.chunk_attention_limited.argtypes = [
         vp, _Strides, i32, i32, vp, vp, _Strides, i64, ctypes.POINTER(_Segment), i32, f32, vp, vp,
@@ -232,6 +238,23 @@ def chunk_attention_planned(q, n_q: int, n_heads: int, k_cache, v_cache, cache_c
         _ptr(q), _strides(q), n_q, n_heads, _ptr(k_cache), _ptr(v_cache), sc,
         cache_capacity_tokens, arr, len(segs), scale, None if p is None else ctypes.byref(p),
         _ptr(out), _strides(out), _ptr(lse), _ptr(workspace), workspace_bytes, _stream(stream)))
+
+
+def chunk_attention_static_capacity() -> int:
+    return int(_load().chunk_attention_static_capacity())
+
+
+def chunk_attention_static(q, n_q: int, n_heads: int, k_cache, v_cache, cache_capacity_tokens: int,
+                           segs: Sequence[Tuple[int, int]], scale: float, out, lse=None, stream=None) -> None:
+    sc = _strides(k_cache)
+    if _strides(v_cache).token != sc.token or _strides(v_cache).head != sc.head:
+        raise CropeError(CROPE_EINVAL, "k_cache and v_cache must share strides")
+    arr = (_Segment * max(1, len(segs)))()
+    for i, (s, n) in enumerate(segs):
+        arr[i].start, arr[i].len = int(s), int(n)
+    _check(_load().chunk_attention_static(
+        _ptr(q), _strides(q), n_q, n_heads, _ptr(k_cache), _ptr(v_cache), sc, cache_capacity_tokens,
+        arr, len(segs), scale, _ptr(out), _strides(out), _ptr(lse), _stream(stream)))
 
 
 def chunk_attention_limited(q, n_q: int, n_heads: int, k_cache, v_cache, cache_capacity_tokens: int,

@@ -1,5 +1,6 @@
 // Host side of the C ABI: argument validation and kernel launches.  No allocation, no
 // synchronisation, no state except a thread-local error string.
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <climits>
@@ -269,6 +270,66 @@ int chunk_attention_planned(const void* q, crope_strides q_strides, int32_t n_q,
   return attention_impl(q, q_strides, n_q, n_heads, k_cache, v_cache, cache_strides, cache_capacity_tokens,
                         segs, n_segs, scale, nullptr, false, plan, out, out_strides, lse_or_null, workspace,
                         workspace_bytes, stream);
+}
+
+}  // extern "C"
+#pragma GCC visibility pop
+
+namespace {
+// Scratch of chunk_attention_static: the partial results of a split key range.  Every GPU the
+// library runs on holds its own copy of this array, at its own address, until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)CROPE_STATIC_SCRATCH_BYTES;
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, once resolved
+
+// Device address of the current GPU's copy of `scratch` (the array's name itself is only a
+// host-side handle, never a pointer a kernel may use).  Resolved once per device.
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(CROPE_ERANGE, "device index %d out of range", dev);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!p) return fail(CROPE_EHIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // every thread resolves the same address
+  }
+  *out = p;
+  return CROPE_OK;
+}
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+size_t chunk_attention_static_capacity(void) { return kStaticScratchBytes; }
+
+int chunk_attention_static(const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
+                           const void* k_cache, const void* v_cache, crope_strides cache_strides,
+                           int64_t cache_capacity_tokens, const crope_kv_segment* segs, int32_t n_segs,
+                           float scale, void* out, crope_strides out_strides, float* lse_or_null,
+                           void* stream) {
+  // the size check comes first: a problem too large for the static buffer touches no GPU state
+  if (n_q > 0 && n_heads > 0 && segs && n_segs >= 1 && n_segs <= crope::kMaxSegments) {
+    int64_t n_keys = 0;
+    for (int i = 0; i < n_segs; ++i) n_keys += segs[i].len > 0 ? segs[i].len : 0;
+    if (n_keys > 0 && n_keys <= ((int64_t)1 << 30)) {
+      const size_t need = crope::attention_workspace_bytes(n_q, n_heads, n_keys, crope::AttnPlan{0, 0});
+      if (need > kStaticScratchBytes)
+        return fail(CROPE_EWORKSPACE,
+                    "chunk_attention_static: this problem needs %zu bytes of scratch, the built-in "
+                    "buffer holds %zu; use chunk_attention with a caller-provided workspace",
+                    need, kStaticScratchBytes);
+    }
+  }
+  void* ws = nullptr;
+  if (int rc = static_scratch(&ws)) return rc;
+  return attention_impl(q, q_strides, n_q, n_heads, k_cache, v_cache, cache_strides, cache_capacity_tokens,
+                        segs, n_segs, scale, nullptr, false, nullptr, out, out_strides, lse_or_null, ws,
+                        kStaticScratchBytes, stream);
 }
 
 int chunk_attention_limited(const void* q, crope_strides q_strides, int32_t n_q, int32_t n_heads,
