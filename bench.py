@@ -44,9 +44,10 @@ def parse():
                     help="query rows of the workload the CPU oracle is timed on (0 = all of them)")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the MFMA-only loop and the plain copy that measure this GPU's own ceilings")
-    ap.add_argument("--input-sets", type=int, default=8,
+    ap.add_argument("--input-sets", type=int, default=0,
                     help="disjoint q/k/v input sets rotated between steps so the append kernel "
-                         "reads from HBM, not from the 256 MB last-level cache")
+                         "reads from HBM, not from the 256 MB last-level cache (0 = as many as "
+                         "it takes to hold 512 MB of inputs, at least 8)")
     return ap.parse_args()
 
 
@@ -75,21 +76,42 @@ def _events_ms(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
+def _graph_ms(torch, fn, reps):
+    """Average duration of fn(i), i < reps, captured once into a HIP graph and replayed between
+    two events on the capture stream."""
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        fn(0)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(reps):
+                fn(i)
+        graph.replay()   # untimed
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        graph.replay()
+        e1.record(stream)
+        torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
 def measure_mfma_ceiling(torch, attn_tflops):
     """What the matrix pipes of THIS GPU sustain with nothing else going on: 8 waves per CU
     issuing only bf16 MFMAs on random operands for about the duration of one attention launch."""
     lib = _ceilings_lib()
-    st = torch.cuda.current_stream().cuda_stream
     ops = torch.randn(lib.ceiling_mfma_operand_bytes() // 2, device="cuda").to(torch.bfloat16)
     sink = torch.zeros(512 * 256, dtype=torch.float32, device="cuda")
     iters = 6000   # ~0.9 ms per launch at 1.6 PFLOP/s
 
     def run(i):
-        rc = lib.ceiling_mfma_launch(ops.data_ptr(), sink.data_ptr(), iters, st)
+        rc = lib.ceiling_mfma_launch(ops.data_ptr(), sink.data_ptr(), iters, torch.cuda.current_stream().cuda_stream)
         assert rc == 0, "ceiling_mfma_launch: hipError %d" % rc
     for i in range(5):
         run(i)
-    ms = min(_events_ms(torch, run, 20) for _ in range(3))
+    ms = min(_graph_ms(torch, run, 20) for _ in range(3))
     tf = lib.ceiling_mfma_flops(iters) / (ms * 1e-3) / 1e12
     return {"ceiling_mfma": {"what": "MFMA-only loop (v_mfma_f32_32x32x16_bf16, random bf16 operands in "
                                      "registers, 8 waves on each of the 256 CUs), measured in this run",
@@ -101,17 +123,17 @@ def measure_copy_ceiling(torch, sb, rope_bytes, rope_gbps, steps):
     """A plain 16-byte-per-lane copy that moves as many bytes as the append kernel (half read,
     half written), sources rotating over as many disjoint buffers as the append's inputs."""
     lib = _ceilings_lib()
-    st = torch.cuda.current_stream().cuda_stream
     half = (int(rope_bytes) // 2 + 15) // 16 * 16
     srcs = [torch.empty(half, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(len(sb.sets))]
     dstb = torch.empty(half, dtype=torch.uint8, device="cuda")
 
     def run(i):
-        rc = lib.ceiling_copy_launch(dstb.data_ptr(), srcs[i % len(srcs)].data_ptr(), half, st)
+        rc = lib.ceiling_copy_launch(dstb.data_ptr(), srcs[i % len(srcs)].data_ptr(), half,
+                                     torch.cuda.current_stream().cuda_stream)
         assert rc == 0, "ceiling_copy_launch: hipError %d" % rc
     for i in range(10):
         run(i)
-    ms = min(_events_ms(torch, run, steps) for _ in range(3))
+    ms = min(_graph_ms(torch, run, steps) for _ in range(3))
     gbps = 2.0 * half / (ms * 1e-3) / 1e9
     return {"ceiling_copy": {"what": "plain device copy, 16 B per lane, %d bytes read + %d written per launch, "
                                      "sources rotating over %d buffers, measured in this run" % (half, half, len(srcs)),
@@ -138,7 +160,8 @@ def main():
     inp = W.make_inputs(cfg)
     # tables, gains, the cache filled the way generation would have (untimed), and
     # args.input_sets copies of the call's inputs at different addresses
-    sb = devutil.StepBuffers(cfg, inp, input_sets=args.input_sets)
+    n_sets = args.input_sets if args.input_sets > 0 else max(8, -(-(512 << 20) // (int(cfg.rope_bytes) // 2)))
+    sb = devutil.StepBuffers(cfg, inp, input_sets=n_sets)
     desc, tab, gq, gk, group = sb.desc, sb.tab, sb.gq, sb.gk, sb.group
     k_cache, v_cache, cap = sb.k_cache, sb.v_cache, sb.cap
     s, n, off, dst = sb.s, sb.n, sb.off, sb.dst
@@ -166,18 +189,15 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
-    # per-kernel average launch duration with events on the launch stream: K back-to-back
-    # launches of one kernel between two events (an event pair around a single 20 us kernel
-    # would add its own few microseconds), same work as the timed steps
+    # per-kernel average launch duration: K back-to-back launches of one kernel (same work as
+    # the timed steps, inputs rotating) captured once into a HIP graph on the launch stream and
+    # replayed between two events, so that no host time per launch enters the figure (a Python
+    # call through the binding costs ~15 us, about as much as one append kernel runs)
     def timed(fn):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(args.steps):
-            fn(i)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / args.steps
+        return _graph_ms(torch, fn, args.steps)
+
+    def timed_eager(fn):   # for calls that include a library GEMM (not captured)
+        return _events_ms(torch, fn, args.steps)
 
     def rope_only(i):
         sb.append(i)
@@ -258,8 +278,8 @@ def main():
             for i in range(20):
                 fused_call(i)
                 unfused_call(i)
-            t_f = min(timed(fused_call) for _ in range(3))
-            t_u = min(timed(unfused_call) for _ in range(3))
+            t_f = min(timed_eager(fused_call) for _ in range(3))
+            t_u = min(timed_eager(unfused_call) for _ in range(3))
             fused[label] = {"ms": round(t_f, 5), "tflops": round(proj_flops / (t_f * 1e-3) / 1e12, 1),
                             "vendor_gemm_then_append_ms": round(t_u, 5)}
         best = fused["norm_per_head"]

@@ -109,6 +109,9 @@ int crope_qk_norm_rotate_append(
   if (in.head < crope::kHeadDim || q_out_strides.head < crope::kHeadDim ||
       cache_strides.head < crope::kHeadDim)
     return fail(CROPE_EINVAL, "head stride smaller than head_dim");
+  // the kernel addresses a row's chunks with 32-bit byte offsets: 63 * stride * 2 + 256 < 2^32
+  if (in.head > (1 << 24) || q_out_strides.head > (1 << 24) || cache_strides.head > (1 << 24))
+    return fail(CROPE_ERANGE, "head stride above 2^24 elements");
   if (grid_h > desc->max_h || grid_w > desc->max_w)
     return fail(CROPE_ERANGE, "grid %dx%d exceeds table extents %dx%d", grid_h, grid_w,
                 desc->max_h, desc->max_w);
@@ -131,6 +134,7 @@ int crope_qk_norm_rotate_append(
   a.per_head_norm = (norm_group == crope::kHeadDim && n_heads > 1) ? 1 : 0;
   a.n_tokens = n_tokens; a.n_heads = n_heads; a.grid_h = grid_h; a.grid_w = grid_w;
   a.start_frame = start_frame; a.token_offset = token_offset;
+  a.div_hw = crope::make_fastdiv((uint32_t)hw); a.div_w = crope::make_fastdiv((uint32_t)grid_w);
   a.q_out = (uint16_t*)q_out; a.qo_tok = q_out_strides.token; a.qo_head = q_out_strides.head;
   a.k_cache = (uint16_t*)k_cache; a.v_cache = (uint16_t*)v_cache;
   a.c_tok = cache_strides.token; a.c_head = cache_strides.head;

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "../../include/crope.h"
+#include "fastdiv.h"
 
 namespace crope {
 
@@ -35,6 +36,7 @@ struct RopeArgs {
   const float *gain_q, *gain_k;
   float eps; int per_head_norm;
   int n_tokens, n_heads, grid_h, grid_w, start_frame, token_offset;
+  FastDiv div_hw, div_w;   // division by grid_h*grid_w and by grid_w
   uint16_t* q_out; int64_t qo_tok, qo_head;
   uint16_t *k_cache, *v_cache; int64_t c_tok, c_head;
   int64_t dst_token;
