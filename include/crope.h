@@ -118,6 +118,29 @@ int crope_qk_norm_rotate_append(
     void* k_cache, void* v_cache, crope_strides cache_strides,
     int64_t cache_capacity_tokens, int64_t dst_token, void* stream);
 
+/* crope_qk_norm_rotate_append whose rotated q is additionally multiplied by q_scale before its
+ * single rounding to bf16 (k, v and every other argument and error as above; q_scale must be
+ * positive and finite).  With q_scale = crope_folded_q_scale(softmax scale) = scale * log2(e)
+ * the attention calls below can be given scale = CROPE_SCALE_FOLDED: the products q.k are then
+ * the softmax exponents themselves and the attention kernel has no per-score multiply left
+ * (Algorithm 3 steps 3 and 6 share the factor; nothing is rounded twice). */
+int crope_qk_norm_rotate_append_qscaled(
+    const crope_table_desc* desc, const float* d_table,
+    const void* q, const void* k, const void* v, crope_strides in,
+    const float* gain_q, const float* gain_k, float eps, int32_t norm_group,
+    int32_t n_tokens, int32_t n_heads, int32_t grid_h, int32_t grid_w,
+    int32_t start_frame, int32_t token_offset, float q_scale,
+    void* q_out, crope_strides q_out_strides,
+    void* k_cache, void* v_cache, crope_strides cache_strides,
+    int64_t cache_capacity_tokens, int64_t dst_token, void* stream);
+
+/* softmax_scale * log2(e), the q_scale that goes with CROPE_SCALE_FOLDED. */
+float crope_folded_q_scale(float softmax_scale);
+
+/* Value of `scale` in the attention calls that says: q was written with
+ * q_scale = crope_folded_q_scale(softmax scale). */
+#define CROPE_SCALE_FOLDED 0.0f
+
 /* Bytes of scratch chunk_attention needs for this problem size (may be 0). */
 size_t chunk_attention_workspace_bytes(int32_t n_q, int32_t n_heads, int64_t n_keys);
 
@@ -132,7 +155,9 @@ size_t chunk_attention_workspace_bytes(int32_t n_q, int32_t n_heads, int64_t n_k
  *   k_cache,v_cache device bf16 caches, strides cache_strides
  *   segs           HOST array of n_segs (1..4) row ranges; 2 when a ring cache wraps.
  *                  Ranges must lie inside [0, cache_capacity_tokens) and have len > 0.
- *   scale          softmax scale (1/sqrt(128) for the model this follows)
+ *   scale          softmax scale (1/sqrt(128) for the model this follows), positive and finite;
+ *                  or CROPE_SCALE_FOLDED when q already carries scale * log2(e)
+ *                  (crope_qk_norm_rotate_append_qscaled), which is the faster path
  *   out            device bf16 [n_q][n_heads][128], strides out_strides
  *   lse_or_null    device fp32 [n_heads][n_q], natural-log sum-exp of the scaled scores
  *   workspace      device scratch of >= chunk_attention_workspace_bytes(...) bytes, 16-byte

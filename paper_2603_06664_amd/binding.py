@@ -87,6 +87,12 @@ def _load():
     lib.crope_qk_norm_rotate_append.argtypes = [
         ctypes.POINTER(_Desc), vp, vp, vp, vp, _Strides, vp, vp, f32, i32, i32, i32, i32, i32,
         i32, i32, vp, _Strides, vp, vp, _Strides, i64, i64, vp]
+    lib.crope_qk_norm_rotate_append_qscaled.restype = ctypes.c_int
+    lib.crope_qk_norm_rotate_append_qscaled.argtypes = [
+        ctypes.POINTER(_Desc), vp, vp, vp, vp, _Strides, vp, vp, f32, i32, i32, i32, i32, i32,
+        i32, i32, f32, vp, _Strides, vp, vp, _Strides, i64, i64, vp]
+    lib.crope_folded_q_scale.restype = ctypes.c_float
+    lib.crope_folded_q_scale.argtypes = [f32]
     lib.chunk_attention_workspace_bytes.restype = ctypes.c_size_t
     lib.chunk_attention_workspace_bytes.argtypes = [i32, i32, i64]
     lib.chunk_attention.restype = ctypes.c_int
@@ -181,6 +187,33 @@ def crope_qk_norm_rotate_append(desc: TableDesc, d_table, q, k, v, gain_q, gain_
         ctypes.byref(d), _ptr(d_table), _ptr(q), _ptr(k), _ptr(v), sin, _ptr(gain_q),
         _ptr(gain_k), eps, norm_group, n_tokens, n_heads, grid_h, grid_w, start_frame,
         token_offset, _ptr(q_out), _strides(q_out), _ptr(k_cache), _ptr(v_cache), sc,
+        cache_capacity_tokens, dst_token, _stream(stream)))
+
+
+CROPE_SCALE_FOLDED = 0.0
+
+
+def crope_folded_q_scale(softmax_scale: float) -> float:
+    return float(_load().crope_folded_q_scale(softmax_scale))
+
+
+def crope_qk_norm_rotate_append_qscaled(desc: TableDesc, d_table, q, k, v, gain_q, gain_k, eps: float,
+                                        norm_group: int, n_tokens: int, n_heads: int, grid_h: int,
+                                        grid_w: int, start_frame: int, token_offset: int, q_scale: float,
+                                        q_out, k_cache, v_cache, cache_capacity_tokens: int, dst_token: int,
+                                        stream=None) -> None:
+    d = desc._c()
+    sin = _strides(q)
+    if _strides(k).token != sin.token or _strides(v).token != sin.token or \
+            _strides(k).head != sin.head or _strides(v).head != sin.head:
+        raise CropeError(CROPE_EINVAL, "q, k, v must share strides")
+    sc = _strides(k_cache)
+    if _strides(v_cache).token != sc.token or _strides(v_cache).head != sc.head:
+        raise CropeError(CROPE_EINVAL, "k_cache and v_cache must share strides")
+    _check(_load().crope_qk_norm_rotate_append_qscaled(
+        ctypes.byref(d), _ptr(d_table), _ptr(q), _ptr(k), _ptr(v), sin, _ptr(gain_q),
+        _ptr(gain_k), eps, norm_group, n_tokens, n_heads, grid_h, grid_w, start_frame,
+        token_offset, q_scale, _ptr(q_out), _strides(q_out), _ptr(k_cache), _ptr(v_cache), sc,
         cache_capacity_tokens, dst_token, _stream(stream)))
 
 

@@ -50,10 +50,14 @@ constexpr int BN = 64;                  // keys per tile
 constexpr int kRowBytes = kHeadDim * 2; // 256 B per key row in LDS (swizzled, unpadded)
 constexpr int kTileBytes = BN * kRowBytes;   // 16 KB
 constexpr float kLog2e = 1.44269504088896340736f;
+constexpr float kLn2 = 0.69314718055994530942f;
 // A query's reference maximum is only raised when a block's maximum exceeds it by more than
-// this many powers of two; until then probabilities may exceed 1 (at most 2^8), which fp32
-// accumulators and bf16's exponent range absorb, and the O rescale is skipped.
+// this many powers of two; until then probabilities may exceed 1, which fp32 accumulators and
+// bf16's exponent range absorb, and the O rescale is skipped.  Whether to look at all is decided
+// from a lane's 16-key share of the block's denominator: above kTrigger some probability is
+// above 2^5, below it none is above 2^9.
 constexpr float kRescaleLog2 = 8.0f;
+constexpr float kTrigger = 512.0f;
 
 struct SplitInfo {
   int n_splits;
@@ -83,6 +87,7 @@ struct PipeState {
   f32x16_t s_a, s_b;   // raw scores: one block being exponentiated, the next being accumulated
   uint32_t p_prev[8];  // bf16 probabilities of the block whose P.V is due
   float m_ref, mc, l_run;
+  f32x16_t seed;       // FOLDED: minus the reference in every element, the S accumulators' start value
 };
 
 struct FragOffsets {
@@ -93,7 +98,13 @@ struct FragOffsets {
 // key0_next: global index of the first key of the block scored by this call (S_{b+1});
 // lim: this lane's query sees keys [0, lim) (the number of visible keys, or less under a
 // per-query limit).
-template <bool DO_S, bool DO_PV, bool DO_SOFTMAX, bool MASK_S>
+// FOLDED: the queries already carry the factor scale*log2(e) (folded into their single bf16
+// rounding by the kernel that wrote them), so the MFMA result is the exponent itself once the
+// accumulators are seeded with minus the reference: no per-score arithmetic in front of the
+// exp.  Otherwise scores are raw and each costs one fma (times scale*log2 e, minus reference).
+// FORCE: this is the first block of the key range; its maximum becomes the reference whatever
+// its value.
+template <bool DO_S, bool DO_PV, bool DO_SOFTMAX, bool MASK_S, bool FOLDED, bool FORCE = false>
 __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_in, f32x16_t& s_out,
                                               const bf16x8_t (&qf)[8],
                                               const uint8_t* k_half,   // K rows of block b+1
@@ -102,8 +113,10 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_i
                                               float c, float tau) {
   f32x16_t s_new;
 #pragma unroll
-  for (int i = 0; i < 16; ++i)   // keys past the end are masked by seeding their scores with -inf
-    s_new[i] = (MASK_S && key0_next + 8 * (i >> 2) + 4 * g + (i & 3) >= lim) ? -INFINITY : 0.f;
+  for (int i = 0; i < 16; ++i) {   // keys past the end are masked by seeding their scores with -inf
+    const float seed = FOLDED ? st.seed[i] : 0.f;
+    s_new[i] = (MASK_S && key0_next + 8 * (i >> 2) + 4 * g + (i & 3) >= lim) ? -INFINITY : seed;
+  }
   uint32_t p_new[8];
   const bf16x2_t ones = {(__bf16)1.0f, (__bf16)1.0f};
   bf16x8_t pb[2];
@@ -111,8 +124,7 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_i
     pb[0] = __builtin_bit_cast(bf16x8_t, make_uint4(st.p_prev[0], st.p_prev[1], st.p_prev[2], st.p_prev[3]));
     pb[1] = __builtin_bit_cast(bf16x8_t, make_uint4(st.p_prev[4], st.p_prev[5], st.p_prev[6], st.p_prev[7]));
   }
-  float l_new = st.l_run;
-  float mx = -INFINITY;
+  float l_blk = 0.f;   // this lane's share of the block's denominator
   // Program order = the order in which the scheduler hands out fragment reads: V first (its
   // MFMAs run first), then K (the S chain closes the block), then the softmax stream.
   if (DO_PV) {
@@ -139,12 +151,12 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_i
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float s0 = s_in[2 * i], s1 = s_in[2 * i + 1];
-      mx = fmaxf(fmaxf(mx, s0), s1);
-      const uint32_t u = pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(s0, c, -st.mc)),
-                                     __builtin_amdgcn_exp2f(fmaf(s1, c, -st.mc)));
+      const uint32_t u = FOLDED ? pack_bf16x2(__builtin_amdgcn_exp2f(s0), __builtin_amdgcn_exp2f(s1))
+                                : pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(s0, c, -st.mc)),
+                                              __builtin_amdgcn_exp2f(fmaf(s1, c, -st.mc)));
       p_new[i] = u;
       // denominator from the rounded values the MFMA will see
-      l_new = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, l_new, false);
+      l_blk = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, l_blk, false);
     }
   }
   // Issue order inside the block: a few fragment reads first, then every MFMA is followed by
@@ -154,7 +166,7 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_i
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // VALU
+      __builtin_amdgcn_sched_group_barrier(0x002, FOLDED ? 1 : 2, 0);   // VALU
       __builtin_amdgcn_sched_group_barrier(0x400, 1, 0);   // TRANS
       if (i < 8) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // DS reads, four MFMAs ahead
     }
@@ -164,29 +176,67 @@ __device__ __forceinline__ void sub_iteration(PipeState& st, const f32x16_t& s_i
     // its first use in the next sub-iteration)
 #pragma unroll
     for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(p_new[i]));
-    asm volatile("" : "+v"(l_new), "+v"(mx));
-    // ---- rare: the block maximum outgrew the reference (always so for the first block)
-    mx = max_across_halves(mx);
-    const bool raise = mx > st.m_ref + tau;
-    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-      const float m_new = raise ? mx : st.m_ref;
-      const float alpha = __builtin_amdgcn_exp2f((st.m_ref - m_new) * c);   // 1 where unchanged, 0 at start
-      st.m_ref = m_new;
-      st.mc = m_new * c;
+    asm volatile("" : "+v"(l_blk));
+    // ---- rare: a probability of this block is large (above 2^5 at least, 2^9 at most), i.e. a
+    // score outgrew the reference; seen from the block's denominator, so that the common case
+    // pays no per-score maximum.  (!(x <= t) is also true for an overflowed, non-finite sum.)
+    const bool big = !(l_blk <= kTrigger);
+    if (FORCE || __builtin_amdgcn_ballot_w64(big) != 0) {
+      float mx = -INFINITY;
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
+      for (int i = 0; i < 8; ++i) mx = fmaxf(fmaxf(mx, s_in[2 * i]), s_in[2 * i + 1]);
+      mx = max_across_halves(mx);
+      if (FOLDED) {
+        // s_in holds exponents relative to the reference: move the reference up by `shift`
+        const bool raise = FORCE || mx > kRescaleLog2;
+        const float shift = raise ? mx : 0.f;
+        if (!FORCE) {   // at the first block O and the denominator are still zero
+          const float alpha = __builtin_amdgcn_exp2f(-shift);   // 1 where unchanged
 #pragma unroll
-        for (int i = 0; i < 16; ++i) st.o_acc[db][i] *= alpha;
-      l_new = st.l_run * alpha;
+          for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t u = pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(s_in[2 * i], c, -st.mc)),
-                                       __builtin_amdgcn_exp2f(fmaf(s_in[2 * i + 1], c, -st.mc)));
-        p_new[i] = u;
-        l_new = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, l_new, false);
+            for (int i = 0; i < 16; ++i) st.o_acc[db][i] *= alpha;
+          st.l_run *= alpha;
+        }
+        st.m_ref += shift;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st.seed[i] = -st.m_ref;
+        if (DO_S) {   // the block in flight was seeded with the old reference
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s_new[i] -= shift;
+        }
+        l_blk = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const uint32_t u = pack_bf16x2(__builtin_amdgcn_exp2f(s_in[2 * i] - shift),
+                                         __builtin_amdgcn_exp2f(s_in[2 * i + 1] - shift));
+          p_new[i] = u;
+          l_blk = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, l_blk, false);
+        }
+      } else {
+        const bool raise = FORCE || mx > st.m_ref + tau;
+        const float m_new = raise ? mx : st.m_ref;
+        if (!FORCE) {
+          const float alpha = __builtin_amdgcn_exp2f((st.m_ref - m_new) * c);   // 1 where unchanged
+#pragma unroll
+          for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) st.o_acc[db][i] *= alpha;
+          st.l_run *= alpha;
+        }
+        st.m_ref = m_new;
+        st.mc = m_new * c;
+        l_blk = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const uint32_t u = pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(s_in[2 * i], c, -st.mc)),
+                                         __builtin_amdgcn_exp2f(fmaf(s_in[2 * i + 1], c, -st.mc)));
+          p_new[i] = u;
+          l_blk = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, u), ones, l_blk, false);
+        }
       }
     }
-    st.l_run = l_new;
+    st.l_run += l_blk;
 #pragma unroll
     for (int i = 0; i < 8; ++i) st.p_prev[i] = p_new[i];
   }
@@ -273,7 +323,7 @@ __device__ __forceinline__ void load_tile(const Loader& L, int tile, uint8_t* ds
 // Iteration T: wait for K of tile T+1 and V of tile T, start the copies of K_{T+2} and V_{T+1}
 // into the two buffers nobody reads any more, then run the two 32-key sub-iterations.
 // On entry st.s_b holds S of block 2T+1 and st.p_prev holds P of block 2T.
-template <int NW, bool MASK_S>
+template <int NW, bool MASK_S, bool FOLDED>
 __device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, const bf16x8_t (&qf)[8],
                                                const FragOffsets& fo, int T, int n_t, uint8_t* k_load,
                                                uint8_t* v_load, const uint8_t* k_read, const uint8_t* v_read,
@@ -283,9 +333,9 @@ __device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, c
   __syncthreads();   // K_{T+1}, V_T have landed; every wave is done with K_T and V_{T-1}
   if (T + 2 < n_t) load_tile<false, NW>(L, T + 2, k_load);
   load_tile<true, NW>(L, T + 1, v_load);
-  sub_iteration<true, true, true, MASK_S>(st, st.s_b, st.s_a, qf, k_read, v_read, fo,
+  sub_iteration<true, true, true, MASK_S, FOLDED>(st, st.s_b, st.s_a, qf, k_read, v_read, fo,
                                           L.key_first + (2 * T + 2) * 32, lim, g, c, tau);
-  sub_iteration<true, true, true, MASK_S>(st, st.s_a, st.s_b, qf, k_read + kHalf, v_read + kHalf, fo,
+  sub_iteration<true, true, true, MASK_S, FOLDED>(st, st.s_a, st.s_b, qf, k_read + kHalf, v_read + kHalf, fo,
                                           L.key_first + (2 * T + 3) * 32, lim, g, c, tau);
 }
 
@@ -295,7 +345,7 @@ __device__ __forceinline__ void tile_iteration(PipeState& st, const Loader& L, c
 // LIMITED: every query carries its own count of leading visible keys (a block-causal or
 // causal prefix mask); every score block is then masked per lane and the key loop stops at the
 // largest limit of the work-group.
-template <int NW, bool LIMITED>
+template <int NW, bool LIMITED, bool FOLDED>
 __global__ __attribute__((amdgpu_flat_work_group_size(64 * NW, 64 * NW), amdgpu_waves_per_eu(2, 2)))
 void attention_kernel(AttnArgs a, SplitInfo sp) {
   constexpr int BM = 32 * NW;   // queries per work-group
@@ -411,7 +461,11 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   for (int i = 0; i < 8; ++i) st.p_prev[i] = 0u;
   const float c = a.scale * kLog2e;   // exp(x*scale) = exp2(x*c)
   const float tau = kRescaleLog2 / c; // in raw score units
-  st.m_ref = -INFINITY;               // reference maximum of raw scores of query n
+  // reference maximum of query n's scores: raw score units (FOLDED: exponent units; the first
+  // block's maximum is added to this 0)
+  st.m_ref = FOLDED ? 0.f : -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) st.seed[i] = 0.f;
   st.mc = 0.f;                        // m_ref * c
   st.l_run = 0.f;                     // this lane's share of the denominator
   const int key_base = tile_begin * BN;
@@ -423,31 +477,37 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   if (n_t > 1) load_tile<false, NW>(L, 1, k_lds1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  sub_iteration<true, false, false, true>(st, st.s_a, st.s_a, qf, k_lds0, nullptr, fo, key_base, lim, g, c, tau);
-  sub_iteration<true, false, false, true>(st, st.s_b, st.s_b, qf, k_lds0 + kHalf, nullptr, fo, key_base + 32, lim,
-                                          g, c, tau);
-  sub_iteration<false, false, true, false>(st, st.s_a, st.s_a, qf, nullptr, nullptr, fo, 0, lim, g, c, tau);
+  sub_iteration<true, false, false, true, FOLDED>(st, st.s_a, st.s_a, qf, k_lds0, nullptr, fo, key_base, lim, g, c,
+                                                  tau);
+  sub_iteration<true, false, false, true, FOLDED>(st, st.s_b, st.s_b, qf, k_lds0 + kHalf, nullptr, fo, key_base + 32,
+                                                  lim, g, c, tau);
+  sub_iteration<false, false, true, false, FOLDED, true>(st, st.s_a, st.s_a, qf, nullptr, nullptr, fo, 0, lim, g, c,
+                                                         tau);
+  if (FOLDED) {   // S_1 was accumulated before there was a reference
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.s_b[i] -= st.m_ref;
+  }
 
   // ---- steady state: iteration T scores tile T+1 (K) and accumulates tile T (V)
   int T = 0;
   if (LIMITED) {   // tiles below every limit of this wave: the unmasked code (same barriers per iteration)
     for (; T + 3 < n_t && T + 2 < n_unmasked; T += 2) {
-      tile_iteration<NW, false>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);
-      tile_iteration<NW, false>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, lim, g, c, tau);
+      tile_iteration<NW, false, FOLDED>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);
+      tile_iteration<NW, false, FOLDED>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, lim, g, c, tau);
     }
   }
   for (; T + 3 < n_t; T += 2) {
-    tile_iteration<NW, LIMITED>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);       // even T
-    tile_iteration<NW, LIMITED>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, lim, g, c, tau);   // odd T
+    tile_iteration<NW, LIMITED, FOLDED>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);       // even T
+    tile_iteration<NW, LIMITED, FOLDED>(st, L, qf, fo, T + 1, n_t, k_lds1, v_lds0, k_lds0, v_lds1, lim, g, c, tau);   // odd T
   }
   if (T + 2 < n_t) {
-    tile_iteration<NW, LIMITED>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);
+    tile_iteration<NW, LIMITED, FOLDED>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);
     ++T;
   }
   // ---- T == n_t - 2 scores the last tile, which may reach beyond the visible keys
   if (T + 1 < n_t) {
-    if (T & 1) tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds1, v_lds0, k_lds0, v_lds1, lim, g, c, tau);
-    else tile_iteration<NW, true>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);
+    if (T & 1) tile_iteration<NW, true, FOLDED>(st, L, qf, fo, T, n_t, k_lds1, v_lds0, k_lds0, v_lds1, lim, g, c, tau);
+    else tile_iteration<NW, true, FOLDED>(st, L, qf, fo, T, n_t, k_lds0, v_lds1, k_lds1, v_lds0, lim, g, c, tau);
     ++T;
   }
   // ---- drain: T == n_t - 1; last tile's V, last block's softmax
@@ -455,8 +515,8 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     const uint8_t* vb = (T & 1) ? v_lds1 : v_lds0;
-    sub_iteration<false, true, true, false>(st, st.s_b, st.s_b, qf, nullptr, vb, fo, 0, lim, g, c, tau);
-    sub_iteration<false, true, false, false>(st, st.s_a, st.s_a, qf, nullptr, vb + kHalf, fo, 0, lim, g, c, tau);
+    sub_iteration<false, true, true, false, FOLDED>(st, st.s_b, st.s_b, qf, nullptr, vb, fo, 0, lim, g, c, tau);
+    sub_iteration<false, true, false, false, FOLDED>(st, st.s_a, st.s_a, qf, nullptr, vb + kHalf, fo, 0, lim, g, c, tau);
   }
   f32x16_t* o_acc = st.o_acc;
   const float m_ref = st.m_ref, l_run = st.l_run;
@@ -478,7 +538,8 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
         w.y = pack_bf16x2(o_acc[db][4 * i4 + 2] * inv_l, o_acc[db][4 * i4 + 3] * inv_l);
         *reinterpret_cast<uint2*>(op + d) = w;
       }
-    if (a.lse && g == 0) a.lse[(int64_t)head * a.n_q + qrow] = m_ref * a.scale + logf(l_tot);
+    if (a.lse && g == 0)
+      a.lse[(int64_t)head * a.n_q + qrow] = FOLDED ? (m_ref + log2f(l_tot)) * kLn2 : m_ref * a.scale + logf(l_tot);
   } else {
     // partial result: unnormalised O (fp32), reference maximum and denominator
     float* ws = reinterpret_cast<float*>(a.workspace);
@@ -512,7 +573,7 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a, SplitInfo sp) 
   const float* ws = reinterpret_cast<const float*>(a.workspace);
   const int64_t rows = (int64_t)a.n_heads * a.n_q;
   const float* ml = ws + (int64_t)sp.n_splits * rows * kHeadDim;
-  const float c = a.scale * kLog2e;
+  const float c = a.folded ? 1.0f : a.scale * kLog2e;   // the partial maxima are exponents already when folded
   float m = -INFINITY;
   for (int s = 0; s < sp.n_splits; ++s) m = fmaxf(m, ml[(s * rows + hq) * 2]);
   float l = 0.f;
@@ -529,7 +590,7 @@ __global__ __launch_bounds__(256) void combine_kernel(AttnArgs a, SplitInfo sp) 
   wv.x = pack_bf16x2(acc.x * inv, acc.y * inv);
   wv.y = pack_bf16x2(acc.z * inv, acc.w * inv);
   *reinterpret_cast<uint2*>(a.out + (int64_t)q * a.o_tok + (int64_t)head * a.o_head + d4 * 4) = wv;
-  if (a.lse && d4 == 0) a.lse[hq] = m * a.scale + logf(l);
+  if (a.lse && d4 == 0) a.lse[hq] = a.folded ? (m + log2f(l)) * kLn2 : m * a.scale + logf(l);
 }
 
 constexpr int kCus = 256;
@@ -572,14 +633,14 @@ AttnPlan choose_plan(int n_q, int n_heads, int64_t n_keys, AttnPlan want) {
   return best;
 }
 
-template <int NW, bool LIMITED>
+template <int NW, bool LIMITED, bool FOLDED>
 hipError_t launch_attention_t(const AttnArgs& a, SplitInfo sp, hipStream_t st) {
   sp.q_tiles = (a.n_q + 32 * NW - 1) / (32 * NW);
   const int64_t total_units = (int64_t)sp.q_tiles * a.n_heads * sp.n_splits;
   if (total_units > (1 << 30)) return hipErrorInvalidValue;
   sp.total_units = (int)total_units;
   sp.units_per_xcd = (sp.total_units + kXcds - 1) / kXcds;
-  hipLaunchKernelGGL((attention_kernel<NW, LIMITED>), dim3(kXcds * sp.units_per_xcd), dim3(64 * NW), 0, st, a, sp);
+  hipLaunchKernelGGL((attention_kernel<NW, LIMITED, FOLDED>), dim3(kXcds * sp.units_per_xcd), dim3(64 * NW), 0, st, a, sp);
   return hipGetLastError();
 }
 
@@ -603,8 +664,13 @@ hipError_t launch_attention(const AttnArgs& a, AttnPlan want, hipStream_t st) {
   const int n_tiles = (int)((a.n_keys + BN - 1) / BN);
   sp.tiles_per_split = (n_tiles + sp.n_splits - 1) / sp.n_splits;
   hipError_t e;
-  if (a.q_limit) e = plan.waves == 8 ? launch_attention_t<8, true>(a, sp, st) : launch_attention_t<4, true>(a, sp, st);
-  else e = plan.waves == 8 ? launch_attention_t<8, false>(a, sp, st) : launch_attention_t<4, false>(a, sp, st);
+  if (a.folded) {
+    if (a.q_limit) e = plan.waves == 8 ? launch_attention_t<8, true, true>(a, sp, st) : launch_attention_t<4, true, true>(a, sp, st);
+    else e = plan.waves == 8 ? launch_attention_t<8, false, true>(a, sp, st) : launch_attention_t<4, false, true>(a, sp, st);
+  } else {
+    if (a.q_limit) e = plan.waves == 8 ? launch_attention_t<8, true, false>(a, sp, st) : launch_attention_t<4, true, false>(a, sp, st);
+    else e = plan.waves == 8 ? launch_attention_t<8, false, false>(a, sp, st) : launch_attention_t<4, false, false>(a, sp, st);
+  }
   if (e != hipSuccess || sp.n_splits == 1) return e;
   const int64_t total = (int64_t)a.n_heads * a.n_q * (kHeadDim / 4);
   hipLaunchKernelGGL(combine_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, sp);

@@ -70,14 +70,19 @@ int crope_build_table(const crope_table_desc* desc, float* d_table, size_t bytes
   return CROPE_OK;
 }
 
-int crope_qk_norm_rotate_append(
+}  // extern "C"
+#pragma GCC visibility pop
+
+namespace {
+int append_impl(
     const crope_table_desc* desc, const float* d_table, const void* q, const void* k,
     const void* v, crope_strides in, const float* gain_q, const float* gain_k, float eps,
     int32_t norm_group, int32_t n_tokens, int32_t n_heads, int32_t grid_h, int32_t grid_w,
-    int32_t start_frame, int32_t token_offset, void* q_out, crope_strides q_out_strides,
+    int32_t start_frame, int32_t token_offset, float q_scale, void* q_out, crope_strides q_out_strides,
     void* k_cache, void* v_cache, crope_strides cache_strides, int64_t cache_capacity_tokens,
     int64_t dst_token, void* stream) {
   if (int rc = check_desc(desc)) return rc;
+  if (!(q_scale > 0.0f) || !(q_scale < 1e30f)) return fail(CROPE_EINVAL, "q_scale must be positive and finite");
   if (!d_table || !q || !k || !v || !gain_q || !gain_k || !q_out || !k_cache || !v_cache)
     return fail(CROPE_EINVAL, "null pointer argument");
   if (n_tokens < 0) return fail(CROPE_EINVAL, "n_tokens is negative");
@@ -132,6 +137,7 @@ int crope_qk_norm_rotate_append(
   a.in_tok = in.token; a.in_head = in.head;
   a.gain_q = gain_q; a.gain_k = gain_k; a.eps = eps;
   a.per_head_norm = (norm_group == crope::kHeadDim && n_heads > 1) ? 1 : 0;
+  a.q_scale = q_scale;
   a.n_tokens = n_tokens; a.n_heads = n_heads; a.grid_h = grid_h; a.grid_w = grid_w;
   a.start_frame = start_frame; a.token_offset = token_offset;
   a.div_hw = crope::make_fastdiv((uint32_t)hw); a.div_w = crope::make_fastdiv((uint32_t)grid_w);
@@ -144,6 +150,36 @@ int crope_qk_norm_rotate_append(
   g_err[0] = 0;
   return CROPE_OK;
 }
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+int crope_qk_norm_rotate_append(
+    const crope_table_desc* desc, const float* d_table, const void* q, const void* k,
+    const void* v, crope_strides in, const float* gain_q, const float* gain_k, float eps,
+    int32_t norm_group, int32_t n_tokens, int32_t n_heads, int32_t grid_h, int32_t grid_w,
+    int32_t start_frame, int32_t token_offset, void* q_out, crope_strides q_out_strides,
+    void* k_cache, void* v_cache, crope_strides cache_strides, int64_t cache_capacity_tokens,
+    int64_t dst_token, void* stream) {
+  return append_impl(desc, d_table, q, k, v, in, gain_q, gain_k, eps, norm_group, n_tokens, n_heads, grid_h,
+                     grid_w, start_frame, token_offset, 1.0f, q_out, q_out_strides, k_cache, v_cache,
+                     cache_strides, cache_capacity_tokens, dst_token, stream);
+}
+
+int crope_qk_norm_rotate_append_qscaled(
+    const crope_table_desc* desc, const float* d_table, const void* q, const void* k,
+    const void* v, crope_strides in, const float* gain_q, const float* gain_k, float eps,
+    int32_t norm_group, int32_t n_tokens, int32_t n_heads, int32_t grid_h, int32_t grid_w,
+    int32_t start_frame, int32_t token_offset, float q_scale, void* q_out, crope_strides q_out_strides,
+    void* k_cache, void* v_cache, crope_strides cache_strides, int64_t cache_capacity_tokens,
+    int64_t dst_token, void* stream) {
+  return append_impl(desc, d_table, q, k, v, in, gain_q, gain_k, eps, norm_group, n_tokens, n_heads, grid_h,
+                     grid_w, start_frame, token_offset, q_scale, q_out, q_out_strides, k_cache, v_cache,
+                     cache_strides, cache_capacity_tokens, dst_token, stream);
+}
+
+float crope_folded_q_scale(float softmax_scale) { return softmax_scale * 1.44269504088896340736f; }
 
 size_t chunk_attention_workspace_bytes(int32_t n_q, int32_t n_heads, int64_t n_keys) {
   if (n_q <= 0 || n_heads <= 0 || n_keys <= 0) return 0;
@@ -182,7 +218,8 @@ int attention_impl(const void* q, crope_strides q_strides, int32_t n_q, int32_t 
   if (n_heads <= 0 || n_heads > 65535) return fail(CROPE_EINVAL, "n_heads out of range");
   if (n_segs < 1 || n_segs > crope::kMaxSegments)
     return fail(CROPE_EINVAL, "n_segs must be 1..%d, got %d", crope::kMaxSegments, n_segs);
-  if (!(scale > 0.0f) || !(scale < 1e30f)) return fail(CROPE_EINVAL, "scale must be positive and finite");
+  // scale == CROPE_SCALE_FOLDED (0): the queries already carry scale*log2(e)
+  if (!(scale >= 0.0f) || !(scale < 1e30f)) return fail(CROPE_EINVAL, "scale must be positive and finite, or CROPE_SCALE_FOLDED");
   if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) ||
       (workspace && !aligned16(workspace)) || (lse_or_null && ((uintptr_t)lse_or_null & 3)))
     return fail(CROPE_EALIGN, "every base pointer must be 16-byte aligned (lse: 4)");
@@ -222,7 +259,7 @@ int attention_impl(const void* q, crope_strides q_strides, int32_t n_q, int32_t 
   a.q_limit = limited ? q_limit : nullptr;
   a.k_cache = (const uint16_t*)k_cache; a.v_cache = (const uint16_t*)v_cache;
   a.c_tok = cache_strides.token; a.c_head = cache_strides.head;
-  a.n_keys = n_keys; a.scale = scale;
+  a.n_keys = n_keys; a.folded = scale == 0.0f ? 1 : 0; a.scale = a.folded ? 1.0f : scale;
   a.out = (uint16_t*)out; a.o_tok = out_strides.token; a.o_head = out_strides.head;
   a.lse = lse_or_null; a.workspace = workspace; a.workspace_bytes = workspace_bytes;
   hipError_t e = crope::launch_attention(a, want, (hipStream_t)stream);

@@ -35,6 +35,7 @@ struct RopeArgs {
   int64_t in_tok, in_head;
   const float *gain_q, *gain_k;
   float eps; int per_head_norm;
+  float q_scale;   // factor on the rotated q (1 for the plain call)
   int n_tokens, n_heads, grid_h, grid_w, start_frame, token_offset;
   FastDiv div_hw, div_w;   // division by grid_h*grid_w and by grid_w
   uint16_t* q_out; int64_t qo_tok, qo_head;
@@ -57,6 +58,7 @@ struct AttnArgs {
   const uint16_t *k_cache, *v_cache; int64_t c_tok, c_head;
   Segments segs; int64_t n_keys;
   float scale;
+  int folded;   // the queries already carry scale*log2(e): the kernels neither multiply nor need `scale`
   uint16_t* out; int64_t o_tok, o_head;
   float* lse;
   void* workspace; size_t workspace_bytes;

@@ -181,6 +181,7 @@ void rope_kernel(RopeArgs a, int heads_per_wave) {
   }
   const float2* tab2 = reinterpret_cast<const float2*>(a.table);
   const float inv_group = 1.0f / (float)(PER_HEAD ? kHeadDim : a.n_heads * kHeadDim);
+  const float out_scale = role == 0 ? a.q_scale : 1.0f;   // folded into 1/rms: no extra arithmetic per element
 
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
@@ -228,7 +229,7 @@ void rope_kernel(RopeArgs a, int heads_per_wave) {
         __syncthreads();
         tot = (part[0] + part[1]) + (part[2] + part[3]);   // fixed order
       }
-      row_scale = __builtin_amdgcn_rsqf(tot * inv_group + a.eps);
+      row_scale = __builtin_amdgcn_rsqf(tot * inv_group + a.eps) * out_scale;
 #pragma unroll
       for (int p = 0; p < 4; ++p) { cs[p] *= row_scale; sn[p] *= row_scale; }
     }
@@ -239,7 +240,7 @@ void rope_kernel(RopeArgs a, int heads_per_wave) {
       if (!valid[it]) continue;
       float c_it[4], s_it[4];
       if (PER_HEAD) {
-        const float hs = __builtin_amdgcn_rsqf(group16_sum(ss[it]) * inv_group + a.eps);
+        const float hs = __builtin_amdgcn_rsqf(group16_sum(ss[it]) * inv_group + a.eps) * out_scale;
 #pragma unroll
         for (int p = 0; p < 4; ++p) { c_it[p] = cs[p] * hs; s_it[p] = sn[p] * hs; }
       } else {

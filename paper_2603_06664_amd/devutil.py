@@ -59,10 +59,15 @@ class StepBuffers:
     sharded workload, the other ranks' rows of the current block, all through
     crope_qk_norm_rotate_append), the current call's raw q, k, v and its outputs."""
 
-    def __init__(self, cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, input_sets: int = 1):
+    def __init__(self, cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, input_sets: int = 1,
+                 folded: bool = True):
+        """folded: the step's append writes q times scale*log2(e) and its attention runs with
+        CROPE_SCALE_FOLDED (the faster pairing); otherwise plain q and an explicit scale."""
         import torch
         from . import binding as P
         self.cfg, self.P = cfg, P
+        self.folded = folded
+        self.q_scale = P.crope_folded_q_scale(SCALE) if folded else 1.0
         H, D = cfg.n_heads, cfg.head_dim
         self.H, self.D = H, D
         self.group = H * D if norm_group is None else norm_group
@@ -103,13 +108,20 @@ class StepBuffers:
     def append(self, i: int = 0):
         cfg, P = self.cfg, self.P
         q, k, v = self.sets[i % len(self.sets)]
-        P.crope_qk_norm_rotate_append(self.desc, self.tab, q, k, v, self.gq, self.gk, cfg.eps, self.group,
-                                      self.n, self.H, cfg.grid_h, cfg.grid_w, self.s, self.off, self.q_rot,
-                                      self.k_cache, self.v_cache, self.cap, self.dst)
+        if self.folded:
+            P.crope_qk_norm_rotate_append_qscaled(self.desc, self.tab, q, k, v, self.gq, self.gk, cfg.eps,
+                                                  self.group, self.n, self.H, cfg.grid_h, cfg.grid_w, self.s,
+                                                  self.off, self.q_scale, self.q_rot, self.k_cache, self.v_cache,
+                                                  self.cap, self.dst)
+        else:
+            P.crope_qk_norm_rotate_append(self.desc, self.tab, q, k, v, self.gq, self.gk, cfg.eps, self.group,
+                                          self.n, self.H, cfg.grid_h, cfg.grid_w, self.s, self.off, self.q_rot,
+                                          self.k_cache, self.v_cache, self.cap, self.dst)
 
     def attention(self):
         self.P.chunk_attention(self.q_rot, self.cfg.n_q, self.H, self.k_cache, self.v_cache, self.cap,
-                               self.segs, SCALE, self.out, self.lse, self.ws, self.ws_bytes)
+                               self.segs, self.P.CROPE_SCALE_FOLDED if self.folded else SCALE, self.out,
+                               self.lse, self.ws, self.ws_bytes)
 
     def step(self, i: int = 0):
         self.append(i)

@@ -76,9 +76,11 @@ def oracle_chain(cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, q_rows
 
 
 # ------------------------------------------------------------------ HIP side
-def hip_chain(cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, want_lse=True):
+def hip_chain(cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, want_lse=True, folded=False):
     """Runs table build, every append call of the schedule, then attention, through the
-    C ABI.  Returns numpy results (bf16 bits widened to fp64 where noted)."""
+    C ABI.  Returns numpy results (bf16 bits widened to fp64 where noted).
+    folded: the current call writes q multiplied by scale*log2(e) (…_append_qscaled) and attention
+    runs with CROPE_SCALE_FOLDED; the returned q_rot has the factor divided out again."""
     import torch
     import paper_2603_06664_amd as P
     H, D = cfg.n_heads, cfg.head_dim
@@ -103,18 +105,26 @@ def hip_chain(cfg: W.ChunkConfig, inp: W.ChunkInputs, norm_group=None, want_lse=
             if scratch_q is None or scratch_q.shape[0] < n:
                 scratch_q = torch.empty((n, H, D), dtype=torch.bfloat16, device="cuda")
             qi, qo = k[row0:row0 + n], scratch_q[:n]
-        P.crope_qk_norm_rotate_append(desc, tab, qi, k[row0:row0 + n], v[row0:row0 + n], gq, gk,
-                                      cfg.eps, group, n, H, cfg.grid_h, cfg.grid_w, s, off, qo,
-                                      k_cache, v_cache, cap, dst_row(cfg, s, off))
+        if folded and is_cur:
+            P.crope_qk_norm_rotate_append_qscaled(desc, tab, qi, k[row0:row0 + n], v[row0:row0 + n], gq, gk,
+                                                  cfg.eps, group, n, H, cfg.grid_h, cfg.grid_w, s, off,
+                                                  P.crope_folded_q_scale(SCALE), qo, k_cache, v_cache, cap,
+                                                  dst_row(cfg, s, off))
+        else:
+            P.crope_qk_norm_rotate_append(desc, tab, qi, k[row0:row0 + n], v[row0:row0 + n], gq, gk,
+                                          cfg.eps, group, n, H, cfg.grid_h, cfg.grid_w, s, off, qo,
+                                          k_cache, v_cache, cap, dst_row(cfg, s, off))
     segs = visible_segments(cfg)
     out = torch.empty_like(q_out)
     lse = torch.empty((H, cfg.n_q), dtype=torch.float32, device="cuda") if want_lse else None
     n_keys = sum(n for _, n in segs)
     ws_bytes = P.chunk_attention_workspace_bytes(cfg.n_q, H, n_keys)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
-    P.chunk_attention(q_out, cfg.n_q, H, k_cache, v_cache, cap, segs, SCALE, out, lse, ws, ws_bytes)
+    P.chunk_attention(q_out, cfg.n_q, H, k_cache, v_cache, cap, segs, P.CROPE_SCALE_FOLDED if folded else SCALE,
+                      out, lse, ws, ws_bytes)
     torch.cuda.synchronize()
-    return dict(q_rot=bits_to_f64(dev_bits(q_out)), k_cache=bits_to_f64(dev_bits(k_cache)),
+    q_unit = P.crope_folded_q_scale(SCALE) if folded else 1.0
+    return dict(q_rot=bits_to_f64(dev_bits(q_out)) / q_unit, k_cache=bits_to_f64(dev_bits(k_cache)),
                 v_cache_bits=dev_bits(v_cache), o=bits_to_f64(dev_bits(out)),
                 lse=lse.cpu().numpy().astype(np.float64) if want_lse else None, segs=segs)
 

@@ -101,6 +101,22 @@ def test_append_rejects_bad_arguments(kwargs, code):
     assert ei.value.message and P.crope_last_error() == ei.value.message
 
 
+@pytest.mark.parametrize("q_scale", [0.0, -0.5, float("nan"), float("inf")])
+def test_qscaled_append_rejects_bad_scale(q_scale):
+    t = _FakeTensor(A, (24, 2, 128))
+    c = _FakeTensor(A, (72, 2, 128))
+    g = _FakeTensor(A, (256,), esize=4)
+    with pytest.raises(P.CropeError) as ei:
+        P.crope_qk_norm_rotate_append_qscaled(P.TableDesc(), _FakeTensor(A, (1,), esize=4), t, t, t, g, g, 1e-6,
+                                              256, 24, 2, 4, 6, 5, 0, q_scale, t, c, c, 72, 48)
+    assert ei.value.code == B.CROPE_EINVAL
+
+
+def test_folded_q_scale_value():
+    assert abs(P.crope_folded_q_scale(128 ** -0.5) - 128 ** -0.5 * 1.4426950408889634) < 1e-7
+    assert P.CROPE_SCALE_FOLDED == 0.0
+
+
 def test_append_zero_tokens_is_a_noop():
     _append(n=0, dst=72)   # valid: writes rows [72, 72)
 
@@ -121,7 +137,8 @@ def _attn(n_q=24, H=2, cap=72, segs=((0, 72),), scale=128 ** -0.5, q_addr=A, ws=
     (dict(segs=((0, 0),)), B.CROPE_EINVAL),
     (dict(segs=()), B.CROPE_EINVAL),
     (dict(segs=((0, 1),) * 5), B.CROPE_EINVAL),
-    (dict(scale=0.0), B.CROPE_EINVAL),
+    (dict(scale=-1.0), B.CROPE_EINVAL),              # 0 is CROPE_SCALE_FOLDED; negative is not a scale
+    (dict(scale=float("inf")), B.CROPE_EINVAL),
     (dict(scale=float("nan")), B.CROPE_EINVAL),
     (dict(q_addr=A + 8), B.CROPE_EALIGN),
     (dict(n_q=-3), B.CROPE_EINVAL),

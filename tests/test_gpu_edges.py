@@ -27,23 +27,37 @@ def _rand_bits(rng, shape, scale=1.0):
     return W.f32_to_bf16_bits((rng.standard_normal(shape) * scale).astype(np.float32))
 
 
-def _attn_case(P, n_q, H, cap, segs, seed, q_scale=1.0, want_lse=True):
+def _folded_q(P, qb):
+    """bf16 queries carrying the factor scale*log2(e), as crope_qk_norm_rotate_append_qscaled would
+    have written them, and the fp64 queries the oracle must see for the same softmax."""
+    c = np.float32(P.crope_folded_q_scale(Hn.SCALE))
+    bits = W.f32_to_bf16_bits(W.bf16_bits_to_f32(qb) * c)
+    return bits, Hn.bits_to_f64(bits) / float(c)
+
+
+FOLDED = pytest.mark.parametrize("folded", [False, True], ids=["scale", "folded"])
+
+
+def _attn_case(P, n_q, H, cap, segs, seed, q_scale=1.0, want_lse=True, folded=False):
     import torch
     import oracle
     rng = np.random.default_rng(seed)
     qb, kb, vb = _rand_bits(rng, (n_q, H, 128), q_scale), _rand_bits(rng, (cap, H, 128)), _rand_bits(rng, (cap, H, 128))
+    q_ref = Hn.bits_to_f64(qb)
+    if folded:
+        qb, q_ref = _folded_q(P, qb)
     q, k, v = Hn.to_dev_bf16(qb), Hn.to_dev_bf16(kb), Hn.to_dev_bf16(vb)
     out = torch.empty_like(q)
     lse = torch.empty((H, n_q), dtype=torch.float32, device="cuda") if want_lse else None
     n_keys = sum(n for _, n in segs)
     wsb = P.chunk_attention_workspace_bytes(n_q, H, n_keys)
     ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
-    P.chunk_attention(q, n_q, H, k, v, cap, segs, Hn.SCALE, out, lse, ws, wsb)
+    P.chunk_attention(q, n_q, H, k, v, cap, segs, P.CROPE_SCALE_FOLDED if folded else Hn.SCALE, out, lse, ws, wsb)
     torch.cuda.synchronize()
     kf, vf = Hn.bits_to_f64(kb), Hn.bits_to_f64(vb)
     kk = np.concatenate([kf[s:s + n] for s, n in segs])
     vv = np.concatenate([vf[s:s + n] for s, n in segs])
-    o_ref, lse_ref = oracle.attention(Hn.bits_to_f64(qb), kk, vv, Hn.SCALE)
+    o_ref, lse_ref = oracle.attention(q_ref, kk, vv, Hn.SCALE)
     got = Hn.bits_to_f64(Hn.dev_bits(out))
     return got, o_ref, (lse.cpu().numpy().astype(np.float64) if want_lse else None), lse_ref
 
@@ -58,28 +72,31 @@ def _attn_case(P, n_q, H, cap, segs, seed, q_scale=1.0, want_lse=True):
     [(100, 32), (0, 16), (148, 16)],
     [(64, 16), (0, 32), (112, 16), (200, 70)],      # the same trap with a fourth segment behind it
 ])
-def test_attention_segment_shapes(P, segs):
-    print("case segs", segs, flush=True)
-    got, ref, lse, lse_ref = _attn_case(P, 77, 3, 400, segs, seed=31)
+@FOLDED
+def test_attention_segment_shapes(P, segs, folded):
+    print("case segs", segs, "folded", folded, flush=True)
+    got, ref, lse, lse_ref = _attn_case(P, 77, 3, 400, segs, seed=31, folded=folded)
     Hn.assert_close("o", got, ref)
     assert np.max(np.abs(lse - lse_ref)) <= 2e-2
 
 
 @pytest.mark.parametrize("n_q", [1, 31, 32, 33, 127, 129, 255, 257])
-def test_attention_query_counts(P, n_q):
-    print("case n_q", n_q, flush=True)
-    got, ref, lse, lse_ref = _attn_case(P, n_q, 2, 333, [(3, 330)], seed=32 + n_q)
+@FOLDED
+def test_attention_query_counts(P, n_q, folded):
+    print("case n_q", n_q, "folded", folded, flush=True)
+    got, ref, lse, lse_ref = _attn_case(P, n_q, 2, 333, [(3, 330)], seed=32 + n_q, folded=folded)
     Hn.assert_close("o", got, ref)
     assert np.max(np.abs(lse - lse_ref)) <= 2e-2
 
 
-def test_attention_extreme_logits(P):
+@FOLDED
+def test_attention_extreme_logits(P, folded):
     """Scores spanning hundreds of powers of two: the reference maximum is raised again and
     again (also by far more than one step), and the softmax saturates.  Scores are exact in
     fp32 (bf16 inputs, fp32 accumulation), so even here only the bf16 rounding of P and O
     separates the kernel from the oracle."""
     for q_scale, seed in ((40.0, 40), (6.0, 42)):
-        got, ref, lse, lse_ref = _attn_case(P, 70, 2, 1000, [(0, 1000)], seed=seed, q_scale=q_scale)
+        got, ref, lse, lse_ref = _attn_case(P, 70, 2, 1000, [(0, 1000)], seed=seed, q_scale=q_scale, folded=folded)
         assert np.all(np.isfinite(got)) and np.all(np.isfinite(lse))
         max_abs, rel_l2, _ = Hn.errors(got, ref)
         print("q_scale %g: max_abs %.3e rel_l2 %.3e" % (q_scale, max_abs, rel_l2), flush=True)
@@ -87,7 +104,8 @@ def test_attention_extreme_logits(P):
         assert np.max(np.abs(lse - lse_ref) / np.maximum(1.0, np.abs(lse_ref))) <= 2e-3
 
 
-def test_attention_increasing_scores(P):
+@FOLDED
+def test_attention_increasing_scores(P, folded):
     """Keys ordered so that later blocks always beat earlier ones (worst case for a lazily
     raised reference)."""
     import torch
@@ -99,13 +117,17 @@ def test_attention_increasing_scores(P):
     ramp = np.linspace(-4.0, 4.0, n_k, dtype=np.float32)[:, None, None]
     kb = W.f32_to_bf16_bits(base * ramp + 0.05 * rng.standard_normal((n_k, H, 128)).astype(np.float32))
     vb = _rand_bits(rng, (n_k, H, 128))
+    q_ref = Hn.bits_to_f64(qb)
+    if folded:
+        qb, q_ref = _folded_q(P, qb)
     q, k, v = Hn.to_dev_bf16(qb), Hn.to_dev_bf16(kb), Hn.to_dev_bf16(vb)
     out = torch.empty_like(q)
     wsb = P.chunk_attention_workspace_bytes(n_q, H, n_k)
     ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
-    P.chunk_attention(q, n_q, H, k, v, n_k, [(0, n_k)], Hn.SCALE, out, None, ws, wsb)
+    P.chunk_attention(q, n_q, H, k, v, n_k, [(0, n_k)], P.CROPE_SCALE_FOLDED if folded else Hn.SCALE, out, None,
+                      ws, wsb)
     torch.cuda.synchronize()
-    o_ref, _ = oracle.attention(Hn.bits_to_f64(qb), Hn.bits_to_f64(kb), Hn.bits_to_f64(vb), Hn.SCALE)
+    o_ref, _ = oracle.attention(q_ref, Hn.bits_to_f64(kb), Hn.bits_to_f64(vb), Hn.SCALE)
     Hn.assert_close("o", Hn.bits_to_f64(Hn.dev_bits(out)), o_ref)
 
 
@@ -162,17 +184,19 @@ def test_rope_rejects_frame_beyond_table(P):
 
 
 @pytest.mark.parametrize("plan", [(4, 0), (8, 0), (4, 3), (8, 7), (0, 2), (4, 16)])
-def test_forced_plans(P, plan):
+@FOLDED
+def test_forced_plans(P, plan, folded):
     """The work-group shape and the key split are normally chosen by the library; reach the
     other shapes through chunk_attention_planned and compare each with the oracle."""
     import torch
     for cfg in (W.ChunkConfig("V1", 71, 3, 9, 11, start_frame=6, n_frames=3, first_kv_frame=0),
                 W.ChunkConfig("V2", 72, 2, 4, 6, start_frame=7, n_frames=1, first_kv_frame=5, cache_frames=3)):
-        print("case", cfg.name, "plan", plan, flush=True)
+        print("case", cfg.name, "plan", plan, "folded", folded, flush=True)
         inp = W.make_inputs(cfg)
         ref = Hn.oracle_chain(cfg, inp)
         from paper_2603_06664_amd.devutil import StepBuffers
-        sb = StepBuffers(cfg, inp)
+        sb = StepBuffers(cfg, inp, folded=folded)
+        scale = P.CROPE_SCALE_FOLDED if folded else Hn.SCALE
         sb.append()
         resolved = P.chunk_attention_choose_plan(cfg.n_q, cfg.n_heads, sb.n_keys, plan)
         assert resolved[0] in (4, 8) and 1 <= resolved[1] <= 16
@@ -185,37 +209,42 @@ def test_forced_plans(P, plan):
         assert (wsb == 0) == (resolved[1] == 1)
         ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
         P.chunk_attention_planned(sb.q_rot, cfg.n_q, cfg.n_heads, sb.k_cache, sb.v_cache, sb.cap, sb.segs,
-                                  Hn.SCALE, plan, sb.out, sb.lse, ws, wsb)
+                                  scale, plan, sb.out, sb.lse, ws, wsb)
         torch.cuda.synchronize()
         Hn.assert_close("o", Hn.bits_to_f64(Hn.dev_bits(sb.out)), ref["o"])
         assert np.max(np.abs(sb.lse.cpu().numpy().astype(np.float64) - ref["lse"])) <= 2e-2
         if wsb:   # a split plan with too little workspace is refused
             with pytest.raises(P.CropeError) as ei:
                 P.chunk_attention_planned(sb.q_rot, cfg.n_q, cfg.n_heads, sb.k_cache, sb.v_cache, sb.cap,
-                                          sb.segs, Hn.SCALE, plan, sb.out, sb.lse, ws, wsb - 16)
+                                          sb.segs, scale, plan, sb.out, sb.lse, ws, wsb - 16)
             assert ei.value.code == -5
 
 
-def _limited_case(P, n_q, H, n_k, limits, seed):
+def _limited_case(P, n_q, H, n_k, limits, seed, folded=False):
     import torch
     import oracle
     rng = np.random.default_rng(seed)
     qb, kb, vb = _rand_bits(rng, (n_q, H, 128)), _rand_bits(rng, (n_k, H, 128)), _rand_bits(rng, (n_k, H, 128))
+    q_ref = Hn.bits_to_f64(qb)
+    if folded:
+        qb, q_ref = _folded_q(P, qb)
     q, k, v = Hn.to_dev_bf16(qb), Hn.to_dev_bf16(kb), Hn.to_dev_bf16(vb)
     out = torch.empty_like(q)
     lse = torch.empty((H, n_q), dtype=torch.float32, device="cuda")
     lim = torch.from_numpy(np.asarray(limits, dtype=np.int32)).cuda()
-    P.chunk_attention_limited(q, n_q, H, k, v, n_k, [(0, n_k)], Hn.SCALE, lim, out, lse)
+    P.chunk_attention_limited(q, n_q, H, k, v, n_k, [(0, n_k)], P.CROPE_SCALE_FOLDED if folded else Hn.SCALE, lim,
+                              out, lse)
     torch.cuda.synchronize()
     # oracle: key m visible to query i iff m < limit_i  <=>  k_block[m] = m <= q_block[i] = limit_i - 1
     lim_c = np.clip(np.asarray(limits), 1, n_k)
-    o_ref, lse_ref = oracle.attention(Hn.bits_to_f64(qb), Hn.bits_to_f64(kb), Hn.bits_to_f64(vb), Hn.SCALE,
+    o_ref, lse_ref = oracle.attention(q_ref, Hn.bits_to_f64(kb), Hn.bits_to_f64(vb), Hn.SCALE,
                                       q_block=(lim_c - 1).astype(np.int32), k_block=np.arange(n_k, dtype=np.int32))
     return Hn.bits_to_f64(Hn.dev_bits(out)), o_ref, lse.cpu().numpy().astype(np.float64), lse_ref
 
 
 @pytest.mark.parametrize("kind", ["block_causal", "token_causal", "ragged", "clamped", "block_causal_long"])
-def test_attention_with_per_query_limits(P, kind):
+@FOLDED
+def test_attention_with_per_query_limits(P, kind, folded):
     """One pass over a whole sequence with the generator's block-causal rule (and other prefix
     masks) against the oracle's masked attention."""
     print("case", kind, flush=True)
@@ -231,7 +260,7 @@ def test_attention_with_per_query_limits(P, kind):
         limits = np.random.default_rng(7).integers(1, n + 1, size=n)
     else:
         limits = np.where(i % 2 == 0, 0, 10 * n)   # out-of-range values are clamped to [1, n]
-    got, ref, lse, lse_ref = _limited_case(P, n, 3, n, limits, seed=80)
+    got, ref, lse, lse_ref = _limited_case(P, n, 3, n, limits, seed=80, folded=folded)
     Hn.assert_close("o", got, ref)
     assert np.max(np.abs(lse - lse_ref)) <= 2e-2
 

@@ -70,12 +70,13 @@ SMALL = [
 
 @pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
 @pytest.mark.parametrize("per_head", [False, True], ids=["normHD", "normD"])
-def test_small_config_every_element(P, cfg, per_head):
-    _say("case %s per_head=%s" % (cfg.name, per_head))
+@pytest.mark.parametrize("folded", [False, True], ids=["scale", "folded"])
+def test_small_config_every_element(P, cfg, per_head, folded):
+    _say("case %s per_head=%s folded=%s" % (cfg.name, per_head, folded))
     group = cfg.head_dim if per_head else cfg.n_heads * cfg.head_dim
     inp = W.make_inputs(cfg)
     ref = Hn.oracle_chain(cfg, inp, norm_group=group)
-    got = Hn.hip_chain(cfg, inp, norm_group=group)
+    got = Hn.hip_chain(cfg, inp, norm_group=group, folded=folded)
     assert got["segs"] == ref["segs"]
     Hn.assert_close("q_rot", got["q_rot"], ref["q_rot"])
     Hn.assert_close("k_cache", got["k_cache"], ref["k_cache"])
@@ -98,14 +99,18 @@ def _sample_rows(n_q, rng, count=40):
     return rows
 
 
-@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5", "R288", "C5P", "C4R", "R960"])
-def test_full_size_config(P, name):
+# the benchmark's pairing (q written with the softmax factor folded in) at every workload; the
+# plain pairing (explicit scale) at the headline workload and the split-key one
+@pytest.mark.parametrize("name,folded", [("C2", True), ("C3", True), ("C4", True), ("C5", True), ("R288", True),
+                                         ("C5P", True), ("C4R", True), ("R960", True), ("C4", False),
+                                         ("C5", False)])
+def test_full_size_config(P, name, folded):
     cfg = W.CONFIGS[name]
-    _say("case %s: n_q=%d n_keys=%d heads=%d" % (name, cfg.n_q, cfg.n_keys, cfg.n_heads))
+    _say("case %s folded=%s: n_q=%d n_keys=%d heads=%d" % (name, folded, cfg.n_q, cfg.n_keys, cfg.n_heads))
     inp = W.make_inputs(cfg)
     # every query row; only the largest workload is sampled
     rows = _sample_rows(cfg.n_q, np.random.default_rng(100 + cfg.seed)) if name == "R960" else list(range(cfg.n_q))
-    got = Hn.hip_chain(cfg, inp)
+    got = Hn.hip_chain(cfg, inp, folded=folded)
     _say("  hip path done")
     ref = Hn.oracle_chain(cfg, inp, q_rows=rows)
     _say("  oracle done (%d of %d query rows)" % (len(rows), cfg.n_q))
