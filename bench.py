@@ -20,14 +20,15 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
-# HBM bytes per launch at workload C4 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
-# by what the same counter reads for a 1 GiB copy (x2.000 and x1.000); the summary with the
-# commands is profiles/chunk_attention_and_rope_C4_pmc.md.  Other workloads report null.
+# HBM bytes per launch at workload C4 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch,
+# mean of the last 20 dispatches of the benchmark's own step), each scaled by what the same counter
+# reads for a 1 GiB copy (x2.000 and x1.000); the summary with the commands is
+# profiles/chunk_attention_and_append_C4_counters.md.  Other workloads report null.
 MEASURED_TRAFFIC_BYTES = {
-    "C4": {"chunk_attention": (162809.3 * 2.000 + 14046.1 * 1.000) * 1024,
-           "crope_qk_norm_rotate_append": (21204.7 * 2.000 + 42120.0 * 1.000) * 1024,
-           # profiles/qkv_project_C4_kernel_trace_and_pmc.md (per-head norm variant)
-           "crope_qkv_project_norm_rotate_append": (76935.5 * 2.000 + 42120.0 * 1.000) * 1024},
+    "C4": {"chunk_attention": (162808.1 * 2.000 + 14280.4 * 1.000) * 1024,
+           "crope_qk_norm_rotate_append": (21209.0 * 2.000 + 42174.6 * 1.000) * 1024,
+           # profiles/qkv_project_C4_kernel_trace_and_counters.md (per-head norm variant)
+           "crope_qkv_project_norm_rotate_append": (76801.1 * 2.000 + 42120.0 * 1.000) * 1024},
 }
 
 

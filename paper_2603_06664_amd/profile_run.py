@@ -47,7 +47,8 @@ def summarize(path: str, last: int) -> None:
         for (name, ctr), v in sorted(by.items()):
             v.sort()
             d = [x for _, x in v[-last:]]
-            print("  %-90s %-24s dispatches %4d  mean %16.1f" % (name[:90], ctr, len(v), sum(d) / len(d)))
+            print("  %-90s %-24s dispatches %4d  mean %16.1f  max of all %16.1f"
+                  % (name[:90], ctr, len(v), sum(d) / len(d), max(x for _, x in v)))
 
 
 def main():
