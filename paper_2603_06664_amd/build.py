@@ -13,6 +13,10 @@ SOURCES = ["crope_api.hip", "rope.hip", "attention.hip", "project.hip"]
 # so that nothing in libcrope.so exists only for the benchmark
 CEILINGS_LIB = os.path.join(HERE, "libcrope_ceilings.so")
 CEILINGS_SOURCE = "ceilings.hip"
+# issue-level microbenchmark (a standalone executable): the instruction-rate figures quoted for the
+# attention kernel's design come from it
+ISSUE_BENCH = os.path.join(HERE, "issue_bench")
+ISSUE_BENCH_SOURCE = "issue_bench.hip"
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
@@ -33,6 +37,9 @@ def build(force: bool = False, verbose: bool = False) -> str:
     objs = []
     procs = []
     cmd = ["hipcc", *FLAGS, "-shared", os.path.join(CSRC, CEILINGS_SOURCE), "-o", CEILINGS_LIB + ".tmp"]
+    procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    cmd = ["hipcc", *[f for f in FLAGS if f not in ("-fPIC", "-fvisibility=hidden")],
+           os.path.join(CSRC, ISSUE_BENCH_SOURCE), "-o", ISSUE_BENCH]
     procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
