@@ -267,6 +267,14 @@ size_t crope_qkv_project_workspace_bytes(int32_t n_tokens, int32_t n_heads, int3
  * bf16 of the remainder in the workspace) and a second pass stores the bf16 rounding of their
  * sum times 1/rms: one rounding of the fp32 value up to 2^-17 relative.
  *
+ * Which path is faster (one MI355X, bf16): this call ties with a vendor GEMM followed by
+ * crope_qk_norm_rotate_append at 12 heads x 4680 tokens with norm_group == 128 (80 against
+ * 79 us) and is the slower one there with the row-wide norm (100 us: the second pass and the
+ * workspace round trip), at 40 heads x 585 tokens (125 against 88 us) and at 18720 tokens; it
+ * is the faster one where the GEMM is small (5 heads x 4680 tokens: 31 against 45 us; 12 heads
+ * x 1728 tokens: 32 against 41 us).  Callers who want the fastest path at the large shapes
+ * should use the two-kernel sequence.
+ *
  *   x              device bf16 [n_tokens][c_in], row stride x_token_stride elements
  *   w_qkv          device bf16 [3*n_heads*128][c_in], contiguous ([out][in] like a linear layer)
  *   bias_or_null   device fp32 [3*n_heads*128]
