@@ -477,6 +477,20 @@ void attention_kernel(AttnArgs a, SplitInfo sp) {
   if (n_t > 1) load_tile<false, NW>(L, 1, k_lds1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  if (q0 >= a.n_q) {
+    // A wave whose 32 rows all lie past the last query (ragged last query tile) does no
+    // arithmetic: it only takes its share of the tile copies and passes the same barriers as
+    // the others (one per tile iteration, one before the drain).
+    for (int T = 0; T + 1 < n_t; ++T) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (T + 2 < n_t) load_tile<false, NW>(L, T + 2, (T & 1) ? k_lds1 : k_lds0);
+      load_tile<true, NW>(L, T + 1, (T & 1) ? v_lds0 : v_lds1);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    return;
+  }
   sub_iteration<true, false, false, true, FOLDED>(st, st.s_a, st.s_a, qf, k_lds0, nullptr, fo, key_base, lim, g, c,
                                                   tau);
   sub_iteration<true, false, false, true, FOLDED>(st, st.s_b, st.s_b, qf, k_lds0 + kHalf, nullptr, fo, key_base + 32,
