@@ -163,6 +163,29 @@ def test_rope_many_tokens_of_many_heads(P, H):
         Hn.assert_close("o", got["o"][rows], ref["o"])
 
 
+@pytest.mark.parametrize("grid,frames,label", [((30, 52), 3, "three tokens per wave, streaming stores"),
+                                               ((40, 60), 1, "two tokens per wave"),
+                                               ((60, 104), 3, "one token per wave, write-back stores (172 MB)")])
+@pytest.mark.parametrize("per_head", [False, True], ids=["normHD", "normD"])
+def test_rope_launch_shapes_both_norms(P, grid, frames, label, per_head):
+    """The append kernel picks tokens per wave and the store policy from the launch size; every
+    such shape with both norm readings, every element of q~ and of the written cache rows."""
+    print("case", grid, frames, label, "per_head", per_head, flush=True)
+    cfg = W.ChunkConfig("RL%dx%d" % grid, 95 + grid[0], 12, grid[0], grid[1], start_frame=0, n_frames=frames,
+                        first_kv_frame=0)
+    group = 128 if per_head else 12 * 128
+    inp = W.make_inputs(cfg)
+    got = Hn.hip_chain(cfg, inp, norm_group=group, want_lse=False, folded=True)
+    import oracle
+    q_ref = oracle.qk_norm_rotate(Hn.bits_to_f64(inp.q), inp.gain_q, cfg.eps, group, cfg.dims, cfg.theta,
+                                  cfg.grid_h, cfg.grid_w, 0, 0)
+    k_ref = oracle.qk_norm_rotate(Hn.bits_to_f64(inp.k), inp.gain_k, cfg.eps, group, cfg.dims, cfg.theta,
+                                  cfg.grid_h, cfg.grid_w, 0, 0)
+    Hn.assert_close("q_rot", got["q_rot"], q_ref)
+    Hn.assert_close("k_cache", got["k_cache"], k_ref)
+    assert np.array_equal(got["v_cache_bits"], inp.v)
+
+
 def test_rope_far_time_positions(P):
     """Frames near the end of a 1024-entry time table: angles of ~1000 rad must still be
     accurate (they are formed in fp64 when the table is built)."""

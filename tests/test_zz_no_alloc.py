@@ -12,12 +12,19 @@ import harness as Hn
 pytestmark = pytest.mark.gpu
 
 
-def _case(P, n_q, H, n_keys, seed, expect_split):
+def _case(P, n_q, H, n_keys, seed, expect_split, folded=False):
     import torch
     import oracle
     rng = np.random.default_rng(seed)
     bits = lambda shape: W.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
     qb, kb, vb = bits((n_q, H, 128)), bits((n_keys, H, 128)), bits((n_keys, H, 128))
+    q_ref = Hn.bits_to_f64(qb)
+    scale = Hn.SCALE
+    if folded:   # q as the q-scaling append call would have written it
+        c = np.float32(P.crope_folded_q_scale(Hn.SCALE))
+        qb = W.f32_to_bf16_bits(W.bf16_bits_to_f32(qb) * c)
+        q_ref = Hn.bits_to_f64(qb) / float(c)
+        scale = P.CROPE_SCALE_FOLDED
     q, k, v = Hn.to_dev_bf16(qb), Hn.to_dev_bf16(kb), Hn.to_dev_bf16(vb)
     segs = [(0, n_keys)]
     wsb = P.chunk_attention_workspace_bytes(n_q, H, n_keys)
@@ -27,14 +34,14 @@ def _case(P, n_q, H, n_keys, seed, expect_split):
     out_ref, out_new = torch.empty_like(q), torch.empty_like(q)
     lse_ref = torch.empty((H, n_q), dtype=torch.float32, device="cuda")
     lse_new = torch.empty_like(lse_ref)
-    P.chunk_attention(q, n_q, H, k, v, n_keys, segs, Hn.SCALE, out_ref, lse_ref, ws, wsb)
+    P.chunk_attention(q, n_q, H, k, v, n_keys, segs, scale, out_ref, lse_ref, ws, wsb)
     torch.cuda.synchronize()
     print("static call: n_q=%d heads=%d keys=%d scratch=%d" % (n_q, H, n_keys, wsb), flush=True)
-    P.chunk_attention_static(q, n_q, H, k, v, n_keys, segs, Hn.SCALE, out_new, lse_new)
+    P.chunk_attention_static(q, n_q, H, k, v, n_keys, segs, scale, out_new, lse_new)
     torch.cuda.synchronize()
     assert np.array_equal(Hn.dev_bits(out_new), Hn.dev_bits(out_ref))
     assert np.array_equal(lse_new.cpu().numpy(), lse_ref.cpu().numpy())
-    o, lse = oracle.attention(Hn.bits_to_f64(qb), Hn.bits_to_f64(kb), Hn.bits_to_f64(vb), Hn.SCALE)
+    o, lse = oracle.attention(q_ref, Hn.bits_to_f64(kb), Hn.bits_to_f64(vb), Hn.SCALE)
     Hn.assert_close("o", Hn.bits_to_f64(Hn.dev_bits(out_new)), o)
     assert np.max(np.abs(lse_new.cpu().numpy().astype(np.float64) - lse)) <= 2e-2
 
@@ -52,6 +59,8 @@ def test_static_scratch_matches_workspace_entry_point():
     _case(P, 70, 2, 5000, seed=502, expect_split=True)
     # a shape that is not split uses no scratch at all
     _case(P, 2100, 16, 400, seed=503, expect_split=False)
+    # and once more through the scratch with the softmax factor folded into q
+    _case(P, 150, 3, 7000, seed=504, expect_split=True, folded=True)
 
 
 def test_static_scratch_rejects_oversized_problem():
