@@ -25,10 +25,10 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 # reads for a 1 GiB copy (x2.000 and x1.000); the summary with the commands is
 # profiles/chunk_attention_and_append_C4_counters.md.  Other workloads report null.
 MEASURED_TRAFFIC_BYTES = {
-    "C4": {"chunk_attention": (162808.1 * 2.000 + 14280.4 * 1.000) * 1024,
-           "crope_qk_norm_rotate_append": (21209.0 * 2.000 + 42174.6 * 1.000) * 1024,
+    "C4": {"chunk_attention": (247622.1 * 2.000 + 14286.7 * 1.000) * 1024,
+           "crope_qk_norm_rotate_append": (21209.0 * 2.000 + 42175.3 * 1.000) * 1024,
            # profiles/qkv_project_C4_kernel_trace_and_counters.md (per-head norm variant)
-           "crope_qkv_project_norm_rotate_append": (76801.1 * 2.000 + 42120.0 * 1.000) * 1024},
+           "crope_qkv_project_norm_rotate_append": (76838.2 * 2.000 + 42120.0 * 1.000) * 1024},
 }
 
 
