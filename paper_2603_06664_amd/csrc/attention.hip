@@ -11,8 +11,9 @@
 // row-major V tile.
 //
 // A work-group is 4 or 8 waves (128 or 256 queries of one head), always two waves per SIMD:
-// a wave's own VALU work does not overlap its own MFMAs on this hardware, only another
-// wave's does.  K and V tiles of 64 keys are copied HBM -> LDS without passing through
+// a wave issues in order, so whenever its next instruction waits (for an MFMA result, an LDS
+// fragment, the barrier) its matrix and vector slots go unused unless a second wave is there
+// to fill them.  K and V tiles of 64 keys are copied HBM -> LDS without passing through
 // registers (global_load_lds, 16 B per lane), double buffered, XOR-swizzled by choosing
 // which global chunk each lane fetches.
 #include "crope_internal.h"
