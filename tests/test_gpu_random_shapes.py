@@ -107,3 +107,46 @@ def test_random_limited_attention(seed):
                                       q_block=(limits - 1).astype(np.int32), k_block=np.arange(n_k, dtype=np.int32))
     Hn.assert_close("o", Hn.bits_to_f64(Hn.dev_bits(out)), o_ref)
     assert np.max(np.abs(lse.cpu().numpy().astype(np.float64) - lse_ref)) <= 2e-2
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_attention_segments_and_plans(seed):
+    """Random query/key counts, 1..4 disjoint cache segments in random order, a random work
+    division forced through chunk_attention_planned and either scale convention, against the
+    oracle over the concatenated segments."""
+    import torch
+    import oracle
+    import paper_2603_06664_amd as P
+    rng = np.random.default_rng(70000 + seed)
+    H = int(rng.choice([1, 2, 3, 5, 8]))
+    n_q = int(rng.integers(1, 1300))
+    cap = int(rng.integers(8, 5000))
+    n_segs = int(rng.integers(1, 5))
+    cuts = np.sort(rng.choice(np.arange(1, cap), size=min(2 * n_segs - 1, cap - 1), replace=False))
+    bounds = np.concatenate([[0], cuts, [cap]])
+    pieces = [(int(bounds[i]), int(bounds[i + 1] - bounds[i])) for i in range(0, len(bounds) - 1, 2)][:n_segs]
+    segs = [pieces[i] for i in rng.permutation(len(pieces))]
+    plan = (int(rng.choice([0, 4, 8])), int(rng.choice([0, 0, 1, 2, 3, 5, 8, 16])))
+    folded = bool(rng.integers(0, 2))
+    n_keys = sum(m for _, m in segs)
+    print("random attention %d: H=%d n_q=%d cap=%d segs=%s plan=%s folded=%d" % (seed, H, n_q, cap, segs, plan, folded),
+          flush=True)
+    bits = lambda shape: W.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    qb, kb, vb = bits((n_q, H, 128)), bits((cap, H, 128)), bits((cap, H, 128))
+    q_ref, scale = Hn.bits_to_f64(qb), Hn.SCALE
+    if folded:   # q as crope_qk_norm_rotate_append_qscaled would have written it
+        c = np.float32(P.crope_folded_q_scale(Hn.SCALE))
+        qb = W.f32_to_bf16_bits(W.bf16_bits_to_f32(qb) * c)
+        q_ref, scale = Hn.bits_to_f64(qb) / float(c), P.CROPE_SCALE_FOLDED
+    q, k, v = Hn.to_dev_bf16(qb), Hn.to_dev_bf16(kb), Hn.to_dev_bf16(vb)
+    out = torch.empty_like(q)
+    lse = torch.empty((H, n_q), dtype=torch.float32, device="cuda")
+    wsb = P.chunk_attention_planned_workspace_bytes(n_q, H, n_keys, plan)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    P.chunk_attention_planned(q, n_q, H, k, v, cap, segs, scale, plan, out, lse, ws, wsb)
+    torch.cuda.synchronize()
+    kf, vf = Hn.bits_to_f64(kb), Hn.bits_to_f64(vb)
+    o_ref, lse_ref = oracle.attention(q_ref, np.concatenate([kf[s:s + m] for s, m in segs]),
+                                      np.concatenate([vf[s:s + m] for s, m in segs]), Hn.SCALE)
+    Hn.assert_close("o", Hn.bits_to_f64(Hn.dev_bits(out)), o_ref)
+    assert np.max(np.abs(lse.cpu().numpy().astype(np.float64) - lse_ref)) <= 2e-2
